@@ -1,0 +1,145 @@
+/*
+ * liblasnet -- C ABI of the MI355X (gfx950) implementation of the coarse-grained
+ * spatially adaptive bottleneck block of "Latency-aware Spatial-wise Dynamic
+ * Networks" (LASNet): masker -> active-patch index list -> gather (+1 pixel of
+ * neighbours) -> conv1x1 / conv3x3 / conv1x1 -> scatter-add into the residual.
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers unless marked "host".  The caller owns every
+ *     buffer; the library allocates nothing that the caller sees and frees nothing.
+ *   - Feature maps are dense NHWC (the channels of one pixel are contiguous).
+ *     dtype LASNET_F32: float.  LASNET_BF16: bfloat16 bit patterns (uint16).
+ *     Weights have the feature dtype, biases and the masker weights are float.
+ *   - BN and the activation are already folded into W*, b* (Sec. 3.4, first paragraph).
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and
+ *     return without synchronising.  `count` is read on the device: there is no host
+ *     round trip between lasnet_masker and lasnet_sparse_bottleneck.
+ *   - Return value: LASNET_OK or a negative lasnet_status.  On error nothing has been
+ *     enqueued and no output buffer has been touched.
+ *   - A process that has no usable gfx950 device gets LASNET_EHIP from every compute
+ *     call; there is no CPU fallback.
+ */
+#ifndef LASNET_H_
+#define LASNET_H_
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define LASNET_API __attribute__((visibility("default")))
+#else
+#define LASNET_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LASNET_OK = 0,
+  LASNET_EINVAL = -1,       /* null pointer, bad dtype, bad S / M                        */
+  LASNET_ESHAPE = -2,       /* S does not divide H or W; out shape/dtype differs from x  */
+  LASNET_EUNSUPPORTED = -3, /* shape outside what the kernels were built for             */
+  LASNET_EALIAS = -4,       /* out aliases x (see lasnet_sparse_bottleneck)              */
+  LASNET_EHIP = -5          /* HIP runtime error (no device, launch failure)             */
+} lasnet_status;
+
+typedef enum { LASNET_F32 = 0, LASNET_BF16 = 1 } lasnet_dtype;
+
+/* Dense NHWC feature map in device memory: element (n,h,w,c) at ((n*H+h)*W+w)*C+c. */
+typedef struct {
+  void* data;
+  int32_t n, h, w, c;
+  int32_t dtype; /* lasnet_dtype */
+} lasnet_tensor;
+
+/* Flags for lasnet_sparse_bottleneck_ex / lasnet_dense_bottleneck. */
+enum {
+  LASNET_POST_RELU = 1,        /* ReLU after the residual add, on active patches only       */
+  LASNET_FORCE_GENERIC = 2,    /* use the shape-generic scalar-FMA kernel (fp32 accumulate,
+                                  no intermediate rounding) even where an MFMA kernel exists */
+  LASNET_SKIP_IDENTITY = 4     /* caller guarantees out already equals x on inactive patches:
+                                  do not copy x to out first                                 */
+};
+
+LASNET_API int lasnet_version(void);
+LASNET_API const char* lasnet_status_string(int status); /* host pointer to a static string */
+
+/*
+ * Masker (Sec. 3.2: pooling to the patch grid, then a 1x1 convolution; App. B.1 eq.: one
+ * output channel and a strict comparison decide a patch; App. B.1 (2): the masker hands
+ * on the list of active patch indices, not a sparse mask).
+ *
+ *   logit[n,gy,gx] = bm + sum_c Wm[c] * mean_{i,j<S} x[n, gy*S+i, gx*S+j, c]
+ *   mask[n,gy,gx]  = logit > thr                  (tie = inactive)
+ *   idx            = ascending flat cell ids  n*G*GW + gy*GW + gx  with mask = 1
+ *   count[0]       = number of such cells
+ *
+ * The logit is accumulated in fp64 from the stored x and Wm; the comparison is done in
+ * fp64.  x: feature map (f32 or bf16).  Wm: [C] float.  mask: [N*G*GW] bytes (0/1).
+ * idx: capacity N*G*GW int32; entries at and beyond count[0] are left untouched.
+ * G = H/S, GW = W/S; S must divide H and W (Sec. 3.2 considers divisors only).
+ */
+LASNET_API int lasnet_masker(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
+                  uint8_t* mask, int32_t* idx, int32_t* count, void* hip_stream);
+
+/* The same fp64 logits as lasnet_masker compares, written out: logits [N*G*GW] double.
+ * For calibrating bm/thr on synthetic inputs and for debugging a mask. */
+LASNET_API int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, float bm, int S,
+                         double* logits, void* hip_stream);
+
+/*
+ * Sparse bottleneck (Sec. 3.1 gather/compute/scatter; Sec. 3.4 and App. B.1 (2),(3):
+ * the gather is fused into the dynamic convolution, the scatter into the residual add;
+ * Sec. 3.1: positions that are not selected keep the block input).
+ *
+ * For every cell id in idx[0 .. count[0]) -- cell (n,gy,gx), pixels h in [gy*S, gy*S+S),
+ * w in [gx*S, gx*S+S) -- and with y1 taken as 0 outside the image:
+ *   y1  = ReLU(b1 + x . W1^T)                          W1 [M][C]
+ *   y2  = ReLU(b2 + conv3x3(y1, W2, stride 1, pad 1))  W2 [M][3][3][M] (out,ky,kx,in), cross-correlation
+ *   out = x + (b3 + y2 . W3^T)                         W3 [C][M]        no ReLU before the add
+ * Every other pixel: out = x, bit for bit.  Neighbour pixels that belong to inactive
+ * patches still feed y1 with their true x.  The result does not depend on the order of
+ * idx; entries must be unique and < N*G*GW (not checked).  idx == NULL means "all cells
+ * active" and count is then ignored (may be NULL).
+ *
+ * M: bottleneck width.  out: same shape and dtype as x, a different buffer: out->data ==
+ * x->data gives LASNET_EALIAS, because a patch updated in place would corrupt the
+ * neighbour read of an adjacent active patch.
+ * bf16: products on the matrix cores with fp32 accumulation; y1, y2 are rounded to bf16
+ * (nearest even) between the convolutions, out is rounded once after the residual add.
+ */
+LASNET_API int lasnet_sparse_bottleneck(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                             int S, int M,
+                             const void* W1, const float* b1,
+                             const void* W2, const float* b2,
+                             const void* W3, const float* b3,
+                             lasnet_tensor* out, void* hip_stream);
+
+/* Same, with LASNET_* flags (see the enum above). */
+LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                                int S, int M,
+                                const void* W1, const float* b1,
+                                const void* W2, const float* b2,
+                                const void* W3, const float* b3,
+                                lasnet_tensor* out, uint32_t flags, void* hip_stream);
+
+/*
+ * The static block (activation rate 1, no masker): out = x + F(x) at every pixel -- the
+ * l_stat that the paper's latency ratio r_l = l_dyn / l_stat is measured against (Sec. 4.2).
+ * Runs the same kernels over tiles that cover the whole map.  flags: LASNET_POST_RELU,
+ * LASNET_FORCE_GENERIC.
+ */
+LASNET_API int lasnet_dense_bottleneck(const lasnet_tensor* x, int M,
+                            const void* W1, const float* b1,
+                            const void* W2, const float* b2,
+                            const void* W3, const float* b3,
+                            lasnet_tensor* out, uint32_t flags, void* hip_stream);
+
+/* Whether (dtype, C, M, S) has a matrix-core kernel (1) or only the generic one (0);
+ * negative status if even the generic kernel cannot take it.  Host-only query. */
+LASNET_API int lasnet_has_fast_path(int dtype, int C, int M, int S);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASNET_H_ */

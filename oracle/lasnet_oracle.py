@@ -12,10 +12,10 @@ the upsampled patch mask to the block's residual branch,
 
 with no gather, no index list inside the block and no tiling.  Layout is NHWC,
 weights are [out][in] (W2: [out][ky][kx][in]) with BN already folded in
-(Sec. 3.4, "general optimization methods").
+(Sec. 3.4, first paragraph).
 
 Readings of passages the paper leaves open (all restated in the design notes):
-  * "a pooling layer" in the masker = average pool, kernel = stride = S.
+  * the masker's pooling (Sec. 3.2 does not say which) = average pool, kernel = stride = S.
   * inference decision = strict `logit > thr` (App. B.1 equation uses `>`;
     thr generalises its 0); a tie is inactive.
   * the 3x3 conv zero-pads conv1's OUTPUT (as the dense ResNet block does).

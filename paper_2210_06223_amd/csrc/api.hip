@@ -1,0 +1,156 @@
+// extern "C" boundary of liblasnet: argument validation and kernel dispatch only.
+#include "common.hpp"
+
+using namespace lasnet;
+
+namespace {
+
+bool device_ok() {
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+int check_tensor(const lasnet_tensor* t) {
+  if (!t) return LASNET_EINVAL;
+  if (t->dtype != LASNET_F32 && t->dtype != LASNET_BF16) return LASNET_EINVAL;
+  if (t->n < 0 || t->h <= 0 || t->w <= 0 || t->c <= 0) return LASNET_ESHAPE;
+  if (t->n > 0 && !t->data) return LASNET_EINVAL;
+  // pixel indices are 32-bit inside the kernels
+  if ((long long)t->n * t->h * t->w >= (1ll << 31)) return LASNET_EUNSUPPORTED;
+  return LASNET_OK;
+}
+
+// Tile side for the static block: the largest of the built S that divides H and W for
+// this (C, M); otherwise the largest divisor the generic kernel can hold in LDS.
+int dense_tile(int dtype, int H, int W, int C, int M, bool force_generic) {
+  if (dtype == LASNET_BF16 && !force_generic)
+    for (int s = 16; s >= 1; --s)
+      if (H % s == 0 && W % s == 0 && mfma_supported(C, M, s)) return s;
+  for (int s = 16; s >= 1; --s)
+    if (H % s == 0 && W % s == 0 && generic_fits(M, s)) return s;
+  return 0;
+}
+
+int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S, int M,
+              const void* W1, const float* b1, const void* W2, const float* b2, const void* W3,
+              const float* b3, lasnet_tensor* out, uint32_t flags, bool dense, void* stream) {
+  int s = check_tensor(x);
+  if (s != LASNET_OK) return s;
+  if (!out) return LASNET_EINVAL;
+  s = check_tensor(out);
+  if (s != LASNET_OK) return s;
+  if (!W1 || !b1 || !W2 || !b2 || !W3 || !b3) return LASNET_EINVAL;
+  if (M <= 0) return LASNET_EINVAL;
+  if (!dense && idx && !count) return LASNET_EINVAL;
+  if (out->n != x->n || out->h != x->h || out->w != x->w || out->c != x->c ||
+      out->dtype != x->dtype)
+    return LASNET_ESHAPE;
+  if (x->n > 0 && out->data == x->data) return LASNET_EALIAS;
+  const bool force_generic = (flags & LASNET_FORCE_GENERIC) != 0;
+  if (dense) {
+    S = dense_tile(x->dtype, x->h, x->w, x->c, M, force_generic);
+    if (S == 0) return LASNET_EUNSUPPORTED;
+  }
+  if (S <= 0) return LASNET_EINVAL;
+  if (x->h % S != 0 || x->w % S != 0) return LASNET_ESHAPE;
+  const bool fast = x->dtype == LASNET_BF16 && !force_generic && mfma_supported(x->c, M, S);
+  if (!fast && !generic_fits(M, S)) return LASNET_EUNSUPPORTED;
+  if (!device_ok()) return LASNET_EHIP;
+  if (x->n == 0) return LASNET_OK;
+
+  Geom g;
+  g.N = x->n; g.H = x->h; g.W = x->w; g.C = x->c; g.M = M; g.S = S;
+  g.G = x->h / S; g.GW = x->w / S; g.P = x->n * g.G * g.GW;
+  const BlockWeights w{W1, b1, W2, b2, W3, b3};
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipSuccess;
+  if (!dense && idx && !(flags & LASNET_SKIP_IDENTITY)) {
+    const size_t bytes = (size_t)x->n * x->h * x->w * x->c * (x->dtype == LASNET_BF16 ? 2 : 4);
+    e = launch_copy(x->data, out->data, bytes, st);
+    if (e != hipSuccess) return LASNET_EHIP;
+  }
+  const bool relu = (flags & LASNET_POST_RELU) != 0;
+  if (fast)
+    e = launch_mfma(g, x->data, idx, count, w, out->data, relu, st);
+  else
+    e = launch_generic(x->dtype, g, x->data, idx, count, w, out->data, relu, st);
+  return e == hipSuccess ? LASNET_OK : LASNET_EHIP;
+}
+
+int masker_common(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
+                  uint8_t* mask, int32_t* idx, int32_t* count, double* logits, void* stream) {
+  int s = check_tensor(x);
+  if (s != LASNET_OK) return s;
+  if (!Wm) return LASNET_EINVAL;
+  if (S <= 0) return LASNET_EINVAL;
+  if (x->h % S != 0 || x->w % S != 0) return LASNET_ESHAPE;
+  if (!device_ok()) return LASNET_EHIP;
+  const hipError_t e = launch_masker(*x, Wm, bm, S, thr, mask, idx, count, logits, (hipStream_t)stream);
+  return e == hipSuccess ? LASNET_OK : LASNET_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lasnet_version(void) { return 100; }
+
+const char* lasnet_status_string(int status) {
+  switch (status) {
+    case LASNET_OK: return "ok";
+    case LASNET_EINVAL: return "invalid argument (null pointer, bad dtype, S or M)";
+    case LASNET_ESHAPE: return "shape mismatch (S must divide H and W; out must match x)";
+    case LASNET_EUNSUPPORTED: return "shape not supported by the built kernels";
+    case LASNET_EALIAS: return "out must not alias x";
+    case LASNET_EHIP: return "HIP runtime error or no gfx950 device";
+    default: return "unknown status";
+  }
+}
+
+int lasnet_masker(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
+                  uint8_t* mask, int32_t* idx, int32_t* count, void* hip_stream) {
+  if (!count) return LASNET_EINVAL;
+  const bool empty = x && x->n == 0;            // an empty batch has no mask or idx storage
+  if (!empty && (!mask || !idx)) return LASNET_EINVAL;
+  return masker_common(x, Wm, bm, S, thr, mask, idx, count, nullptr, hip_stream);
+}
+
+int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, float bm, int S, double* logits,
+                         void* hip_stream) {
+  if (!logits) return LASNET_EINVAL;
+  return masker_common(x, Wm, bm, S, 0.f, nullptr, nullptr, nullptr, logits, hip_stream);
+}
+
+int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                                int S, int M, const void* W1, const float* b1, const void* W2,
+                                const float* b2, const void* W3, const float* b3,
+                                lasnet_tensor* out, uint32_t flags, void* hip_stream) {
+  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, out, flags, false, hip_stream);
+}
+
+int lasnet_sparse_bottleneck(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S,
+                             int M, const void* W1, const float* b1, const void* W2,
+                             const float* b2, const void* W3, const float* b3, lasnet_tensor* out,
+                             void* hip_stream) {
+  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, out, 0u, false, hip_stream);
+}
+
+int lasnet_dense_bottleneck(const lasnet_tensor* x, int M, const void* W1, const float* b1,
+                            const void* W2, const float* b2, const void* W3, const float* b3,
+                            lasnet_tensor* out, uint32_t flags, void* hip_stream) {
+  return run_block(x, nullptr, nullptr, 0, M, W1, b1, W2, b2, W3, b3, out,
+                   flags & (LASNET_POST_RELU | LASNET_FORCE_GENERIC), true, hip_stream);
+}
+
+int lasnet_has_fast_path(int dtype, int C, int M, int S) {
+  if (dtype != LASNET_F32 && dtype != LASNET_BF16) return LASNET_EINVAL;
+  if (C <= 0 || M <= 0 || S <= 0) return LASNET_EINVAL;
+  if (dtype == LASNET_BF16 && mfma_supported(C, M, S)) return 1;
+  return generic_fits(M, S) ? 0 : LASNET_EUNSUPPORTED;
+}
+
+}  // extern "C"

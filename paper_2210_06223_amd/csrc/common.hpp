@@ -1,0 +1,47 @@
+// Shared declarations of liblasnet's translation units (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lasnet.h"
+
+namespace lasnet {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Geometry of one call, by value into every kernel.
+struct Geom {
+  int N, H, W, C, M, S;
+  int G, GW;       // patch grid: G = H/S rows, GW = W/S columns
+  int P;           // N*G*GW cells
+};
+
+struct BlockWeights {
+  const void* W1; const float* b1;
+  const void* W2; const float* b2;
+  const void* W3; const float* b3;
+};
+
+// ---- launchers (each returns a hipError_t from the launch, never synchronises) ----
+hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int S, float thr,
+                         uint8_t* mask, int32_t* idx, int32_t* count, double* logits,
+                         hipStream_t st);
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+
+// Generic scalar-FMA kernel: any C, M; S limited by LDS. Returns hipErrorInvalidValue if
+// the tile does not fit in LDS.
+bool generic_fits(int M, int S);
+hipError_t launch_generic(int dtype, const Geom& g, const void* x, const int32_t* idx,
+                          const int32_t* count, const BlockWeights& w, void* out, bool post_relu,
+                          hipStream_t st);
+
+// Matrix-core kernel: only for the (C, M, S) it was instantiated for.
+bool mfma_supported(int C, int M, int S);
+hipError_t launch_mfma(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
+                       const BlockWeights& w, void* out, bool post_relu, hipStream_t st);
+
+}  // namespace lasnet

@@ -1,0 +1,86 @@
+"""No-GPU checks of the boundary: the library loads, exports what include/lasnet.h declares,
+and rejects bad arguments on the host before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2210_06223_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lasnet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"LASNET_API\s+[\w\s\*]+?\b(lasnet_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(B.EXPORTS), names
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert B.lasnet_version() >= 100
+    assert L.lasnet_status_string(0) == b"ok"
+    assert b"alias" in L.lasnet_status_string(B.LASNET_EALIAS)
+
+
+def _t(n=1, h=8, w=8, c=16, dtype=B.LASNET_F32, data=0x1000):
+    return B.lasnet_tensor(data, n, h, w, c, dtype)
+
+
+def test_masker_argument_errors():
+    L = B.lib()
+    x = _t()
+    p = ctypes.c_void_p(0x2000)
+    call = lambda xx, wm, S, m=p, i=p, c=p: L.lasnet_masker(xx, wm, 0.0, S, 0.0, m, i, c, None)
+    assert call(None, p, 2) == B.LASNET_EINVAL
+    assert call(ctypes.byref(x), None, 2) == B.LASNET_EINVAL
+    assert call(ctypes.byref(x), p, 0) == B.LASNET_EINVAL
+    assert call(ctypes.byref(x), p, 3) == B.LASNET_ESHAPE          # 3 does not divide 8
+    assert call(ctypes.byref(x), p, 2, m=None) == B.LASNET_EINVAL
+    assert call(ctypes.byref(x), p, 2, c=None) == B.LASNET_EINVAL
+    bad = _t(dtype=7)
+    assert call(ctypes.byref(bad), p, 2) == B.LASNET_EINVAL
+    assert L.lasnet_masker_logits(ctypes.byref(x), p, 0.0, 2, None, None) == B.LASNET_EINVAL
+
+
+def test_block_argument_errors():
+    L = B.lib()
+    p = ctypes.c_void_p(0x2000)
+    x, o = _t(), _t(data=0x9000)
+    w = [p] * 6
+
+    def call(xx, oo, S=2, M=4, idx=p, cnt=p, ws=w):
+        return L.lasnet_sparse_bottleneck(ctypes.byref(xx), idx, cnt, S, M, *ws, ctypes.byref(oo), None)
+
+    assert call(x, x) == B.LASNET_EALIAS
+    assert call(x, _t(h=4, data=0x9000)) == B.LASNET_ESHAPE
+    assert call(x, _t(dtype=B.LASNET_BF16, data=0x9000)) == B.LASNET_ESHAPE
+    assert call(x, o, S=3) == B.LASNET_ESHAPE
+    assert call(x, o, S=0) == B.LASNET_EINVAL
+    assert call(x, o, M=0) == B.LASNET_EINVAL
+    assert call(x, o, cnt=None) == B.LASNET_EINVAL                 # idx without count
+    assert call(x, o, ws=[p, None, p, p, p, p]) == B.LASNET_EINVAL
+    big = _t(h=16, w=16, c=4096)                                   # generic tile cannot hold M=8192 in LDS
+    assert call(big, _t(h=16, w=16, c=4096, data=0x9000), S=16, M=8192) == B.LASNET_EUNSUPPORTED
+
+
+def test_fast_path_query():
+    import torch
+    assert B.lasnet_has_fast_path(torch.bfloat16, 1024, 256, 2) == 1
+    assert B.lasnet_has_fast_path(torch.bfloat16, 512, 128, 4) == 1
+    assert B.lasnet_has_fast_path(torch.bfloat16, 256, 64, 8) == 1
+    assert B.lasnet_has_fast_path(torch.float32, 1024, 256, 2) == 0
+    assert B.lasnet_has_fast_path(torch.bfloat16, 64, 16, 4) == 0
+    assert B.lasnet_has_fast_path(torch.float32, 64, 8192, 16) == B.LASNET_EUNSUPPORTED
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    x = torch.zeros((1, 4, 4, 8))
+    with pytest.raises(ValueError):
+        B.lasnet_masker(x, torch.zeros(8), 0.0, 2)

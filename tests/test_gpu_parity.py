@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Integer outputs (mask, idx, count) and inactive positions must be bit-exact; block outputs
+within 1e-4 relative (fp32) / 2e-2 relative (bf16 storage, fp32 accumulate).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lasnet_oracle as O
+from paper_2210_06223_amd import binding as B
+from paper_2210_06223_amd import synth
+from tests import _util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _cfg(base, **kw):
+    return synth.CONFIGS[base].with_(**kw)
+
+
+def _oracle_w(inp):
+    d = inp.f64
+    return (d["W1"], d["b1"], d["W2"], d["b2"], d["W3"], d["b3"])
+
+
+# ------------------------------------------------------------------ masker
+MASKER_CASES = [
+    _cfg("tiny_f32"),
+    _cfg("stage3_b1"),
+    _cfg("stage3_b128", N=5, name="stage3_n5"),
+    _cfg("stage1_b64", N=2, name="stage1_n2"),
+    _cfg("stage2_b128", N=3, name="stage2_n3"),
+    synth.BlockConfig("odd_c20_s3_f32", 2, 6, 9, 20, 12, 3, "f32", 0.5, 21),     # scalar-load path
+    synth.BlockConfig("odd_c20_s1_bf16", 2, 5, 7, 20, 12, 1, "bf16", 0.3, 22),
+    synth.BlockConfig("pixel_s1_manycells", 8, 32, 32, 8, 8, 1, "f32", 0.37, 23),  # P = 8192: 8 compaction rounds
+    synth.BlockConfig("layer_skip_sH", 3, 8, 8, 16, 8, 8, "bf16", 0.34, 24),       # S = H: one cell per image
+]
+
+
+@pytest.mark.parametrize("cfg", MASKER_CASES, ids=lambda c: c.name)
+def test_masker_matches_oracle_bit_exact(cfg):
+    _say("masker", cfg)
+    inp = synth.make_block_inputs(cfg)
+    k = int(round(cfg.r * cfg.P))
+    bm = U.calibrate(inp, k)
+    d = U.dev_inputs(inp)
+    mask_o, idx_o, count_o, logits_o = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+    assert count_o == k
+    idx = torch.full((cfg.P,), -7, dtype=torch.int32, device="cuda")
+    mask, idx, count = B.lasnet_masker(d["x"], d["Wm"], bm, cfg.S, 0.0, idx=idx)
+    logits = B.lasnet_masker_logits(d["x"], d["Wm"], bm, cfg.S)
+    torch.cuda.synchronize()
+    assert int(count.item()) == count_o
+    assert np.array_equal(mask.cpu().numpy(), mask_o)
+    idx_h = idx.cpu().numpy()
+    assert np.array_equal(idx_h[:count_o], idx_o)
+    assert (idx_h[count_o:] == -7).all()                      # tail untouched
+    assert np.allclose(logits.cpu().numpy(), logits_o, rtol=1e-12, atol=1e-13)
+
+
+def test_masker_threshold_and_extremes():
+    cfg = _cfg("stage2_b128", N=2)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    for k, thr in ((0, 0.0), (cfg.P, 0.0), (cfg.P // 3, 0.125), (7, -0.5)):
+        bm = U.calibrate(inp, k, thr)
+        mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, thr)
+        assert count_o == k
+        mask, idx, count = B.lasnet_masker(d["x"], d["Wm"], bm, cfg.S, thr)
+        torch.cuda.synchronize()
+        assert int(count.item()) == k
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+        assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
+
+
+def test_masker_empty_batch():
+    x = torch.zeros((0, 8, 8, 16), dtype=torch.bfloat16, device="cuda")
+    Wm = torch.zeros(16, device="cuda")
+    count = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    _, _, count = B.lasnet_masker(x, Wm, 0.0, 2, count=count)
+    torch.cuda.synchronize()
+    assert int(count.item()) == 0
+
+
+# ------------------------------------------------------------------ block
+def _run_case(cfg, k=None, idx_np=None, flags=0, order="ascending", use_masker=True):
+    """One parity case.  Either the masker picks k cells (bias from the oracle's logits) or
+    idx_np is fed directly.  Returns nothing; asserts."""
+    _say("block", cfg, "k", k, "flags", flags, "order", order, "masker", use_masker)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    w = U.weights(d)
+    if use_masker:
+        bm = U.calibrate(inp, k)
+        mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+        mask, idx, count = B.lasnet_masker(d["x"], d["Wm"], bm, cfg.S, 0.0)
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+    else:
+        mask_o = np.zeros(cfg.P, np.uint8)
+        mask_o[idx_np] = 1
+        mask_o = mask_o.reshape(cfg.N, cfg.G, cfg.GW)
+        idx = torch.full((cfg.P,), 0, dtype=torch.int32, device="cuda")
+        idx[: len(idx_np)] = torch.from_numpy(idx_np).cuda()
+        count = torch.tensor([len(idx_np)], dtype=torch.int32, device="cuda")
+    out = torch.full_like(d["x"], 777.0)                     # poison: every element must be written
+    B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *w, out=out, flags=flags)
+    torch.cuda.synchronize()
+    ref = O.sparse_bottleneck(inp.f64["x"], mask_o, cfg.S, *_oracle_w(inp),
+                              post_relu=bool(flags & B.LASNET_POST_RELU))
+    up = np.broadcast_to(O.upsample_mask(mask_o, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(out, ref, d["x"], up, cfg.dtype, cfg.name)
+    return out
+
+
+def test_tiny_f32_config():
+    _run_case(_cfg("tiny_f32"), k=8)
+
+
+GENERIC_CASES = [
+    synth.BlockConfig("gen_f32_c20_m12_s3", 2, 6, 9, 20, 12, 3, "f32", 0.5, 31),
+    synth.BlockConfig("gen_bf16_c24_m8_s2", 3, 4, 6, 24, 8, 2, "bf16", 0.5, 32),
+    synth.BlockConfig("gen_f32_s1_pixel", 1, 5, 5, 16, 8, 1, "f32", 0.4, 33),
+    synth.BlockConfig("gen_bf16_sH_layerskip", 3, 4, 4, 32, 16, 4, "bf16", 0.34, 34),
+]
+
+
+@pytest.mark.parametrize("cfg", GENERIC_CASES, ids=lambda c: c.name)
+def test_generic_kernel_odd_shapes(cfg):
+    _run_case(cfg, k=int(round(cfg.r * cfg.P)))
+    _run_case(cfg, k=int(round(cfg.r * cfg.P)), flags=B.LASNET_POST_RELU)
+
+
+# every matrix-core instantiation, small N: several workgroup tiles and a ragged last tile
+MFMA_CASES = [
+    (_cfg("stage3_b128", N=3, name="s3_S2"), 71),             # 147 cells, 71 active: 8 full tiles + 7
+    (_cfg("stage3_b128", N=3, S=7, name="s3_S7"), 5),         # 12 cells
+    (_cfg("stage2_b128", N=2, name="s2_S4"), 49),             # 98 cells, PPW=4 -> ragged
+    (_cfg("stage2_b128", N=2, S=7, name="s2_S7"), 17),        # 32 cells, PPW=2 -> ragged
+    (_cfg("stage1_b64", N=1, name="s1_S8"), 20),              # 49 cells
+    (_cfg("stage1_b64", N=1, S=4, name="s1_S4"), 118),        # 196 cells (Table 1 block: S=4, r=0.6), ragged
+    (_cfg("stage1_b64", N=1, S=7, name="s1_S7"), 31),         # 64 cells, ragged
+]
+
+
+@pytest.mark.parametrize("cfg,k", MFMA_CASES, ids=lambda v: getattr(v, "name", str(v)))
+def test_mfma_kernel_matches_oracle(cfg, k):
+    assert B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, cfg.S) == 1
+    _run_case(cfg, k=k)
+
+
+@pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5],
+                         ids=lambda v: getattr(v, "name", str(v)))
+def test_mfma_extremes_and_flags(cfg, k):
+    _run_case(cfg, k=0)                                        # ratio 0: identity, bit-exact
+    _run_case(cfg, k=cfg.P)                                    # ratio 1: every patch active
+    _run_case(cfg, k=1)
+    _run_case(cfg, k=k, flags=B.LASNET_POST_RELU)
+    _run_case(cfg, k=k, flags=B.LASNET_FORCE_GENERIC)          # scalar kernel on the same shape
+
+
+@pytest.mark.parametrize("structure", ["iid", "blob"])
+def test_index_order_does_not_matter_and_direct_lists(structure):
+    cfg = _cfg("stage2_b128", N=4, name="s2_lists")
+    asc = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=5, structure=structure)
+    shf = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=5, structure=structure, order="shuffled")
+    assert sorted(shf.tolist()) == asc.tolist() and shf.tolist() != asc.tolist()
+    a = _run_case(cfg, idx_np=asc, use_masker=False)
+    b = _run_case(cfg, idx_np=shf, use_masker=False, order="shuffled")
+    assert np.array_equal(U.bits(a), U.bits(b))
+
+
+def test_all_active_null_index_list_equals_dense_oracle():
+    cfg = _cfg("stage3_b128", N=2, name="s3_null_idx")
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    out = torch.full_like(d["x"], 777.0)
+    B.lasnet_sparse_bottleneck(d["x"], None, None, cfg.S, *U.weights(d), out=out)
+    torch.cuda.synchronize()
+    ref = O.dense_bottleneck(inp.f64["x"], *_oracle_w(inp))
+    U.assert_block_close(out, ref, d["x"], np.ones(ref.shape, bool), cfg.dtype, cfg.name)
+
+
+DENSE_CASES = [
+    _cfg("tiny_f32"),
+    _cfg("stage3_b128", N=2, name="dense_s3"),
+    _cfg("stage2_b128", N=1, name="dense_s2"),
+    _cfg("stage1_b64", N=1, name="dense_s1"),
+    synth.BlockConfig("dense_gen_bf16", 2, 6, 4, 24, 8, 2, "bf16", 1.0, 41),
+]
+
+
+@pytest.mark.parametrize("cfg", DENSE_CASES, ids=lambda c: c.name)
+def test_dense_block_matches_oracle(cfg):
+    _say("dense", cfg)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    for flags in (0, B.LASNET_POST_RELU):
+        out = torch.full_like(d["x"], 777.0)
+        B.lasnet_dense_bottleneck(d["x"], *U.weights(d), out=out, flags=flags)
+        torch.cuda.synchronize()
+        ref = O.dense_bottleneck(inp.f64["x"], *_oracle_w(inp), post_relu=bool(flags))
+        U.assert_block_close(out, ref, d["x"], np.ones(ref.shape, bool), cfg.dtype, cfg.name)
+
+
+def test_skip_identity_flag_leaves_inactive_untouched():
+    cfg = _cfg("stage1_b64", N=1, name="s1_skipid")
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    idx_np = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.4, seed=9)
+    idx = torch.from_numpy(idx_np).cuda()
+    count = torch.tensor([len(idx_np)], dtype=torch.int32, device="cuda")
+    out = torch.full_like(d["x"], 5.0)
+    B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), out=out,
+                               flags=B.LASNET_SKIP_IDENTITY)
+    torch.cuda.synchronize()
+    mask = np.zeros(cfg.P, np.uint8); mask[idx_np] = 1
+    up = O.upsample_mask(mask.reshape(cfg.N, cfg.G, cfg.GW), cfg.S).astype(bool)
+    o = U.to_f64(out)
+    assert (o[~up] == 5.0).all() and not (o[up] == 5.0).all()
+
+
+def test_errors_on_device_tensors():
+    cfg = _cfg("tiny_f32")
+    d = U.dev_inputs(synth.make_block_inputs(cfg))
+    idx = torch.zeros(cfg.P, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.LasnetError) as e:
+        B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), out=d["x"])
+    assert e.value.status == B.LASNET_EALIAS
+    with pytest.raises(B.LasnetError) as e:
+        B.lasnet_sparse_bottleneck(d["x"], idx, count, 3, *U.weights(d))
+    assert e.value.status == B.LASNET_ESHAPE
+
+
+# ------------------------------------------------------------------ full size, as bench.py launches it
+def test_headline_workload_full_size_matches_oracle():
+    """ResNet-101 stage 3, 14x14x1024, M=256, S=2, N=128, r=0.5: masker -> index list -> block,
+    device-resident count, every output element against the oracle."""
+    cfg = synth.CONFIGS["stage3_b128"]
+    _run_case(cfg, k=cfg.P // 2)
