@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the LASNet sparse-bottleneck hot path on one MI355X.
+
+One "step" = the whole path over one synthetic batch that is already resident in HBM:
+lasnet_masker (pool -> logit -> threshold -> index list) followed by
+lasnet_sparse_bottleneck (identity copy, gather + conv1 / conv3x3 / conv3 + scatter-add),
+with the active-patch count staying on the device.  Default workload: ResNet-101 stage-3
+bottleneck, 14x14x1024, mid 256, S=2, batch 128, bf16, masker calibrated to r = 0.5.
+
+Prints ONE JSON line: whole-job images/s, plus
+  roofline      the fused bottleneck kernel against the bf16 MFMA peak on ACTIVE FLOPs
+                (r * N * H*W * 34*M^2; halo recompute is never credited), its duration
+                measured here with events on the launch stream;
+  cpu_baseline  the numpy fp64 oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries under profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="stage3_b128",
+                    help="stage3_b128 (headline) | stage2_b128 | stage1_b64 | stage3_b1")
+    ap.add_argument("--ratio", type=float, default=None, help="activation ratio (default: the workload's)")
+    ap.add_argument("--nbuf", type=int, default=6,
+                    help="distinct x/out buffer pairs rotated over, so that steps see HBM-cold data")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-torch-dense", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the block alone over r in {0.1,.25,.5,.75,1} (index lists fed directly)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by image with no exchange; "
+              "see DESIGN.md). --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2210_06223_amd import binding as B
+    from paper_2210_06223_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    B.lib()  # fail loudly if the library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = synth.CONFIGS[args.workload]
+    if args.ratio is not None:
+        cfg = cfg.with_(r=args.ratio)
+    inp = synth.make_block_inputs(cfg, want_f64=False)
+
+    def to_dev(k, v):
+        if cfg.dtype == "bf16" and k in ("x", "W1", "W2", "W3"):
+            return torch.from_numpy(v.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(v).to(dev)
+
+    d = {k: to_dev(k, v) for k, v in inp.dev.items()}
+    w = (d["W1"], d["b1"], d["W2"], d["b2"], d["W3"], d["b3"])
+    S, P = cfg.S, cfg.P
+
+    # Masker bias for the target ratio, calibrated from the library's own fp64 logits.
+    logits0 = B.lasnet_masker_logits(d["x"], d["Wm"], 0.0, S).cpu().numpy()
+    k_target = int(round(cfg.r * P))
+    bm, margin = synth.bias_for_count(logits0, k_target)
+
+    nbuf = max(1, args.nbuf)
+    xs = [d["x"]] + [d["x"].clone() for _ in range(nbuf - 1)]
+    outs = [torch.empty_like(d["x"]) for _ in range(nbuf)]
+    mask = torch.empty((cfg.N, cfg.G, cfg.GW), dtype=torch.uint8, device=dev)
+    idx = torch.empty((P,), dtype=torch.int32, device=dev)
+    count = torch.zeros((1,), dtype=torch.int32, device=dev)
+
+    def step(i):
+        x, out = xs[i % nbuf], outs[i % nbuf]
+        B.lasnet_masker(x, d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count)
+        B.lasnet_sparse_bottleneck(x, idx, count, S, *w, out=out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    images_per_s = cfg.N * args.steps / dt
+    n_active = int(count.item())
+
+    # ---- per-kernel durations, events on the launch stream (torch's current stream) ----
+    def timed(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i in range(reps):
+            ev[i][0].record()
+            fn(i)
+            ev[i][1].record()
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) for a, b in ev)
+        return {"mean_ms": float(np.mean(t)), "median_ms": t[len(t) // 2], "p10_ms": t[len(t) // 10],
+                "p90_ms": t[(len(t) * 9) // 10]}
+
+    reps = max(20, min(args.steps, 200))
+    # the fused kernel alone: same launch as inside the step, identity copy skipped (outs already hold x)
+    fused_t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf],
+                                                         flags=B.LASNET_SKIP_IDENTITY), reps)
+    block_t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf]), reps)
+    masker_t = timed(lambda i: B.lasnet_masker(xs[i % nbuf], d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count), reps)
+    dense_t = timed(lambda i: B.lasnet_dense_bottleneck(xs[i % nbuf], *w, out=outs[i % nbuf]), reps)
+
+    torch_dense = None
+    if not args.no_torch_dense and cfg.dtype == "bf16":
+        try:
+            import torch.nn.functional as F
+            W1c = d["W1"][:, :, None, None].contiguous(memory_format=torch.channels_last)
+            W2c = d["W2"].permute(0, 3, 1, 2)            # [M,M,3,3] view, channels-last strides
+            W3c = d["W3"][:, :, None, None].contiguous(memory_format=torch.channels_last)
+            b1c, b2c, b3c = (d[k].to(torch.bfloat16) for k in ("b1", "b2", "b3"))
+
+            def torch_block(i):
+                xin = xs[i % nbuf].permute(0, 3, 1, 2)   # NCHW view of NHWC memory
+                y = F.relu(F.conv2d(xin, W1c, b1c))
+                y = F.relu(F.conv2d(y, W2c, b2c, padding=1))
+                return xin + F.conv2d(y, W3c, b3c)
+
+            with torch.no_grad():
+                for i in range(5):
+                    torch_block(i)
+                torch.cuda.synchronize()
+                torch_dense = timed(torch_block, reps)
+        except Exception as e:  # the yardstick is optional
+            torch_dense = {"error": repr(e)[:200]}
+
+    flops_img = cfg.H * cfg.W * (2 * cfg.C * cfg.M + 18 * cfg.M * cfg.M + 2 * cfg.M * cfg.C)
+    active_flops = n_active * S * S * (flops_img / (cfg.H * cfg.W))
+    fused_s = fused_t["mean_ms"] * 1e-3
+    achieved_tflops = active_flops / fused_s / 1e12
+    esize = 2 if cfg.dtype == "bf16" else 4
+    x_bytes = cfg.N * cfg.H * cfg.W * cfg.C * esize
+    dense_best = dense_t["mean_ms"]
+    if torch_dense and "mean_ms" in torch_dense:
+        dense_best = min(dense_best, torch_dense["mean_ms"])
+
+    sweep = None
+    if args.sweep:
+        sweep = []
+        for r in (0.1, 0.25, 0.5, 0.75, 1.0):
+            for structure in ("iid", "blob"):
+                il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, r, seed=cfg.seed, structure=structure)
+                idx_r = torch.zeros((P,), dtype=torch.int32, device=dev)
+                idx_r[: len(il)] = torch.from_numpy(il).to(dev)
+                cnt_r = torch.tensor([len(il)], dtype=torch.int32, device=dev)
+                t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx_r, cnt_r, S, *w, out=outs[i % nbuf]), reps)
+                sweep.append({"r_mean": r, "structure": structure, "active": len(il), "block_ms": t["mean_ms"],
+                              "latency_ratio_vs_dense": t["mean_ms"] / dense_best})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, inp, bm)
+
+    result = {
+        "metric": "sparse bottleneck images/s at r=%.2g (masker + index list + fused block)" % cfg.r,
+        "value": images_per_s,
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: ResNet-101 bottleneck %dx%dx%d mid %d, S=%d, batch %d, r=%.3f (%d of %d patches)"
+                   % (cfg.name, cfg.H, cfg.W, cfg.C, cfg.M, S, cfg.N, n_active / P, n_active, P),
+                   "buffers_rotated": nbuf, "masker_margin": margin},
+        "active_tflops_whole_step": active_flops / (ms_per_step * 1e-3) / 1e12,
+        "speedup_vs_dense": dense_best / block_t["mean_ms"],
+        "kernels_ms": {"masker+compaction": masker_t, "copy+fused_block": block_t, "fused_block": fused_t,
+                       "dense_own": dense_t, "dense_torch_miopen": torch_dense},
+        "hbm_floor_ms": 2 * x_bytes / (PEAK_HBM_GBS * 1e9) * 1e3,
+        "roofline": {"bound": "mfma", "kernel": "fused_bneck_kernel", "achieved": achieved_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                     "active_flops_per_launch": active_flops, "avg_launch_ms": fused_t["mean_ms"]},
+        "cpu_baseline": cpu,
+    }
+    if sweep is not None:
+        result["ratio_sweep"] = sweep
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, inp, bm):
+    """The oracle as it stands (numpy fp64), on a bounded sample of the same workload."""
+    from oracle import lasnet_oracle as O
+    from paper_2210_06223_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    f = lambda k: (synth.bf16_bits_to_f32(inp.dev[k]) if inp.dev[k].dtype == np.uint16 else inp.dev[k])
+    wts = [f(k).astype(np.float64) for k in ("W1", "b1", "W2", "b2", "W3", "b3")]
+    Wm = inp.dev["Wm"].astype(np.float64)
+
+    def run(n):
+        x = f("x")[:n].astype(np.float64)
+        t0 = time.perf_counter()
+        mask, idx, cnt, _ = O.masker(x, Wm, bm, cfg.S, 0.0)
+        O.sparse_bottleneck(x, mask, cfg.S, *wts)
+        return time.perf_counter() - t0
+
+    n = min(cfg.N, 2)
+    t = run(n)                                   # also warms the BLAS threads
+    n = int(max(1, min(cfg.N, n * 10.0 / max(t, 1e-3))))   # aim at ~10 s of CPU work
+    t = run(n)
+    return {"value": n / t, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of %d images of the same workload, numpy fp64 dense block then mask, %.2f s" % (n, cfg.N, t)}
+
+
+if __name__ == "__main__":
+    main()
