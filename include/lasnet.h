@@ -6,7 +6,8 @@
  *
  * Conventions for every entry point
  *   - All pointers are DEVICE pointers unless marked "host".  The caller owns every
- *     buffer; the library allocates nothing that the caller sees and frees nothing.
+ *     buffer; the library allocates nothing that the caller sees and frees nothing (its
+ *     one internal buffer is described under "Weight repacking").
  *   - Feature maps are dense NHWC (the channels of one pixel are contiguous).
  *     dtype LASNET_F32: float.  LASNET_BF16: bfloat16 bit patterns (uint16).
  *     Weights have the feature dtype, biases and the masker weights are float.
@@ -22,6 +23,7 @@
 #ifndef LASNET_H_
 #define LASNET_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #if defined(__GNUC__)
@@ -122,6 +124,34 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
                                 const void* W2, const float* b2,
                                 const void* W3, const float* b3,
                                 lasnet_tensor* out, uint32_t flags, void* hip_stream);
+
+/*
+ * Weight repacking for the matrix-core kernels.  Those kernels read W1, W2, W3 from ONE
+ * buffer in which the weights are laid out fragment by fragment in the order the waves
+ * consume them.  lasnet_sparse_bottleneck[_ex] and lasnet_dense_bottleneck take the plain
+ * tensors and repack them on every call, on the caller's stream, into device memory the
+ * library owns (one buffer per device and stream, allocated with hipMalloc on first use
+ * and kept until the process ends -- so those entry points cannot be stream-captured on
+ * their first call).  Weights of an inference model do not change, so a caller can instead
+ * repack once, like it folded BN once (Sec. 3.4), and pass the result to
+ * lasnet_sparse_bottleneck_packed, which allocates nothing:
+ *   bytes = lasnet_packed_weights_bytes(dtype, C, M, S)   host query; 0 = this shape has no
+ *                                                         matrix-core kernel
+ *   lasnet_pack_weights(..., packed, stream)              packed: caller's device buffer
+ * The layout depends on (C, M, S); a packed buffer is only valid for the shape it was
+ * made for.  lasnet_sparse_bottleneck_packed is otherwise lasnet_sparse_bottleneck_ex
+ * (same semantics, flags LASNET_POST_RELU and LASNET_SKIP_IDENTITY) and returns
+ * LASNET_EUNSUPPORTED for shapes or dtypes without a matrix-core kernel.
+ */
+LASNET_API size_t lasnet_packed_weights_bytes(int dtype, int C, int M, int S);
+LASNET_API int lasnet_pack_weights(int dtype, int C, int M, int S, const void* W1, const void* W2,
+                                   const void* W3, void* packed, void* hip_stream);
+LASNET_API int lasnet_sparse_bottleneck_packed(const lasnet_tensor* x, const int32_t* idx,
+                                               const int32_t* count, int S, int M,
+                                               const void* packed, const float* b1,
+                                               const float* b2, const float* b3,
+                                               lasnet_tensor* out, uint32_t flags,
+                                               void* hip_stream);
 
 /*
  * The static block (activation rate 1, no masker): out = x + F(x) at every pixel -- the

@@ -11,7 +11,9 @@ from typing import Optional, Tuple
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblasnet.so")
+# LASNET_LIBRARY overrides the in-tree library (e.g. an instrumented build of the same sources).
+_LIB_PATH = os.environ.get("LASNET_LIBRARY") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "liblasnet.so")
 _lib = None
 
 LASNET_F32, LASNET_BF16 = 0, 1
@@ -21,7 +23,8 @@ LASNET_OK, LASNET_EINVAL, LASNET_ESHAPE, LASNET_EUNSUPPORTED, LASNET_EALIAS, LAS
 EXPORTS = (
     "lasnet_version", "lasnet_status_string", "lasnet_masker", "lasnet_masker_logits",
     "lasnet_sparse_bottleneck", "lasnet_sparse_bottleneck_ex", "lasnet_dense_bottleneck",
-    "lasnet_has_fast_path",
+    "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
+    "lasnet_sparse_bottleneck_packed",
 )
 
 
@@ -64,6 +67,13 @@ def lib() -> ctypes.CDLL:
         L.lasnet_dense_bottleneck.argtypes = [tp, ip, vp, vp, vp, vp, vp, vp, tp, ctypes.c_uint32, vp]
         L.lasnet_has_fast_path.restype = ip
         L.lasnet_has_fast_path.argtypes = [ip, ip, ip, ip]
+        L.lasnet_packed_weights_bytes.restype = ctypes.c_size_t
+        L.lasnet_packed_weights_bytes.argtypes = [ip, ip, ip, ip]
+        L.lasnet_pack_weights.restype = ip
+        L.lasnet_pack_weights.argtypes = [ip, ip, ip, ip, vp, vp, vp, vp, vp]
+        L.lasnet_sparse_bottleneck_packed.restype = ip
+        L.lasnet_sparse_bottleneck_packed.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, tp,
+                                                      ctypes.c_uint32, vp]
         _lib = L
     return _lib
 
@@ -193,4 +203,51 @@ def lasnet_dense_bottleneck(x: torch.Tensor, W1, b1, W2, b2, W3, b3,
     st = lib().lasnet_dense_bottleneck(ctypes.byref(d), M, *w, ctypes.byref(o), int(flags),
                                        _stream(stream))
     _check(st, "lasnet_dense_bottleneck")
+    return out
+
+
+def lasnet_pack_weights(S: int, W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor,
+                        packed: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Repack W1 [M,C], W2 [M,3,3,M], W3 [C,M] (bf16) for the matrix-core kernel of (C, M, S)."""
+    M, C = W1.shape
+    for n, t in (("W1", W1), ("W2", W2), ("W3", W3)):
+        if t.dtype != torch.bfloat16 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("%s must be a contiguous bfloat16 device tensor" % n)
+    if tuple(W2.shape) != (M, 3, 3, M) or tuple(W3.shape) != (C, M):
+        raise ValueError("weights: W1 [M,C], W2 [M,3,3,M], W3 [C,M]")
+    nbytes = lib().lasnet_packed_weights_bytes(LASNET_BF16, int(C), int(M), int(S))
+    if nbytes == 0:
+        _check(LASNET_EUNSUPPORTED, "lasnet_pack_weights")
+    if packed is None:
+        packed = torch.empty((nbytes // 2,), dtype=torch.bfloat16, device=W1.device)
+    elif packed.numel() * packed.element_size() < nbytes or not packed.is_cuda:
+        raise ValueError("packed buffer too small")
+    st = lib().lasnet_pack_weights(LASNET_BF16, int(C), int(M), int(S), _ptr(W1), _ptr(W2), _ptr(W3),
+                                   _ptr(packed), _stream(stream))
+    _check(st, "lasnet_pack_weights")
+    return packed
+
+
+def lasnet_sparse_bottleneck_packed(x: torch.Tensor, idx: Optional[torch.Tensor],
+                                    count: Optional[torch.Tensor], S: int, M: int,
+                                    packed: torch.Tensor, b1, b2, b3,
+                                    out: Optional[torch.Tensor] = None, flags: int = 0,
+                                    stream=None) -> torch.Tensor:
+    d = _as_tensor_desc(x)
+    if out is None:
+        out = torch.empty_like(x)
+    o = _as_tensor_desc(out)
+    for n, t in (("idx", idx), ("count", count)):
+        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    need = lib().lasnet_packed_weights_bytes(LASNET_BF16, int(x.shape[3]), int(M), int(S))
+    if need and packed.numel() * packed.element_size() < need:
+        raise ValueError("packed buffer too small for this shape")
+    if b1.numel() != M or b2.numel() != M or b3.numel() != x.shape[3]:
+        raise ValueError("biases: b1 [M], b2 [M], b3 [C]")
+    st = lib().lasnet_sparse_bottleneck_packed(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), int(M),
+                                               _ptr(packed), _ptr(_f32(b1, "b1")), _ptr(_f32(b2, "b2")),
+                                               _ptr(_f32(b3, "b3")), ctypes.byref(o), int(flags),
+                                               _stream(stream))
+    _check(st, "lasnet_sparse_bottleneck_packed")
     return out

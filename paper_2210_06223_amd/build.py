@@ -28,8 +28,8 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
-    bdir = os.path.join(PKG, "_build")
+def build_library(verbose: bool = True, extra_flags=(), out: str = LIB, build_dir: str = "") -> str:
+    bdir = build_dir or os.path.join(PKG, "_build")
     os.makedirs(bdir, exist_ok=True)
     cc = hipcc()
 
@@ -46,15 +46,15 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    tmp = LIB + ".tmp"
+    tmp = out + ".tmp"
     r = subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
+    os.replace(tmp, out)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":

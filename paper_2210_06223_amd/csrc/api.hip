@@ -1,9 +1,43 @@
 // extern "C" boundary of liblasnet: argument validation and kernel dispatch only.
 #include "common.hpp"
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 using namespace lasnet;
 
 namespace {
+
+// Device memory the library owns: one buffer per (device, stream) for the repacked weights
+// of calls that pass raw W1/W2/W3.  Grown on demand, kept until the process ends.  Work on
+// one stream is ordered, so calls on the same stream may share it; calls on different
+// streams get different buffers.
+struct Workspace { void* ptr = nullptr; size_t cap = 0; };
+std::mutex g_ws_mu;
+std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+void* get_workspace(hipStream_t st, size_t bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  std::lock_guard<std::mutex> lock(g_ws_mu);
+  Workspace& w = g_ws[std::make_pair(dev, st)];
+  if (w.cap < bytes) {
+    if (w.ptr) {
+      if (hipStreamSynchronize(st) != hipSuccess) return nullptr;   // earlier calls still read it
+      (void)hipFree(w.ptr);
+      w.ptr = nullptr;
+      w.cap = 0;
+    }
+    if (hipMalloc(&w.ptr, bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      w.ptr = nullptr;
+      return nullptr;
+    }
+    w.cap = bytes;
+  }
+  return w.ptr;
+}
 
 bool device_ok() {
   int n = 0;
@@ -35,15 +69,18 @@ int dense_tile(int dtype, int H, int W, int C, int M, bool force_generic) {
   return 0;
 }
 
+// packed != nullptr: the caller passes repacked weights (W1..W3 unused).
 int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S, int M,
               const void* W1, const float* b1, const void* W2, const float* b2, const void* W3,
-              const float* b3, lasnet_tensor* out, uint32_t flags, bool dense, void* stream) {
+              const float* b3, const void* packed, lasnet_tensor* out, uint32_t flags, bool dense,
+              void* stream) {
   int s = check_tensor(x);
   if (s != LASNET_OK) return s;
   if (!out) return LASNET_EINVAL;
   s = check_tensor(out);
   if (s != LASNET_OK) return s;
-  if (!W1 || !b1 || !W2 || !b2 || !W3 || !b3) return LASNET_EINVAL;
+  if (!b1 || !b2 || !b3) return LASNET_EINVAL;
+  if (!packed && (!W1 || !W2 || !W3)) return LASNET_EINVAL;
   if (M <= 0) return LASNET_EINVAL;
   if (!dense && idx && !count) return LASNET_EINVAL;
   if (out->n != x->n || out->h != x->h || out->w != x->w || out->c != x->c ||
@@ -58,6 +95,7 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   if (S <= 0) return LASNET_EINVAL;
   if (x->h % S != 0 || x->w % S != 0) return LASNET_ESHAPE;
   const bool fast = x->dtype == LASNET_BF16 && !force_generic && mfma_supported(x->c, M, S);
+  if (packed && !fast) return LASNET_EUNSUPPORTED;
   if (!fast && !generic_fits(M, S)) return LASNET_EUNSUPPORTED;
   if (!device_ok()) return LASNET_EHIP;
   if (x->n == 0) return LASNET_OK;
@@ -68,6 +106,13 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   const BlockWeights w{W1, b1, W2, b2, W3, b3};
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipSuccess;
+  if (fast && !packed) {
+    void* ws = get_workspace(st, mfma_packed_bytes(x->c, M, S));
+    if (!ws) return LASNET_EHIP;
+    e = launch_pack(x->c, M, S, W1, W2, W3, ws, st);
+    if (e != hipSuccess) return LASNET_EHIP;
+    packed = ws;
+  }
   if (!dense && idx && !(flags & LASNET_SKIP_IDENTITY)) {
     const size_t bytes = (size_t)x->n * x->h * x->w * x->c * (x->dtype == LASNET_BF16 ? 2 : 4);
     e = launch_copy(x->data, out->data, bytes, st);
@@ -75,7 +120,7 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   }
   const bool relu = (flags & LASNET_POST_RELU) != 0;
   if (fast)
-    e = launch_mfma(g, x->data, idx, count, w, out->data, relu, st);
+    e = launch_mfma(g, x->data, idx, count, packed, b1, b2, b3, out->data, relu, st);
   else
     e = launch_generic(x->dtype, g, x->data, idx, count, w, out->data, relu, st);
   return e == hipSuccess ? LASNET_OK : LASNET_EHIP;
@@ -129,20 +174,44 @@ int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t* idx, cons
                                 int S, int M, const void* W1, const float* b1, const void* W2,
                                 const float* b2, const void* W3, const float* b3,
                                 lasnet_tensor* out, uint32_t flags, void* hip_stream) {
-  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, out, flags, false, hip_stream);
+  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, nullptr, out, flags, false,
+                   hip_stream);
+}
+
+size_t lasnet_packed_weights_bytes(int dtype, int C, int M, int S) {
+  if (dtype != LASNET_BF16 || C <= 0 || M <= 0 || S <= 0) return 0;
+  return mfma_packed_bytes(C, M, S);
+}
+
+int lasnet_pack_weights(int dtype, int C, int M, int S, const void* W1, const void* W2,
+                        const void* W3, void* packed, void* hip_stream) {
+  if (!W1 || !W2 || !W3 || !packed) return LASNET_EINVAL;
+  if (lasnet_packed_weights_bytes(dtype, C, M, S) == 0) return LASNET_EUNSUPPORTED;
+  if (!device_ok()) return LASNET_EHIP;
+  return launch_pack(C, M, S, W1, W2, W3, packed, (hipStream_t)hip_stream) == hipSuccess ? LASNET_OK
+                                                                                         : LASNET_EHIP;
+}
+
+int lasnet_sparse_bottleneck_packed(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                                    int S, int M, const void* packed, const float* b1,
+                                    const float* b2, const float* b3, lasnet_tensor* out,
+                                    uint32_t flags, void* hip_stream) {
+  if (!packed) return LASNET_EINVAL;
+  return run_block(x, idx, count, S, M, nullptr, b1, nullptr, b2, nullptr, b3, packed, out,
+                   flags & ~(uint32_t)LASNET_FORCE_GENERIC, false, hip_stream);
 }
 
 int lasnet_sparse_bottleneck(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S,
                              int M, const void* W1, const float* b1, const void* W2,
                              const float* b2, const void* W3, const float* b3, lasnet_tensor* out,
                              void* hip_stream) {
-  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, out, 0u, false, hip_stream);
+  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, nullptr, out, 0u, false, hip_stream);
 }
 
 int lasnet_dense_bottleneck(const lasnet_tensor* x, int M, const void* W1, const float* b1,
                             const void* W2, const float* b2, const void* W3, const float* b3,
                             lasnet_tensor* out, uint32_t flags, void* hip_stream) {
-  return run_block(x, nullptr, nullptr, 0, M, W1, b1, W2, b2, W3, b3, out,
+  return run_block(x, nullptr, nullptr, 0, M, W1, b1, W2, b2, W3, b3, nullptr, out,
                    flags & (LASNET_POST_RELU | LASNET_FORCE_GENERIC), true, hip_stream);
 }
 

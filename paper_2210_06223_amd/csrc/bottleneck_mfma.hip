@@ -1,27 +1,42 @@
 // Fused sparse bottleneck on the gfx950 matrix cores (bf16 in, fp32 accumulate).
 //
-// One workgroup owns PPW consecutive entries of the active-patch index list and runs the
-// whole block for them without leaving the CU (Sec. 3.4 / App. B.1: gather fused into the
-// dynamic convolution, scatter fused into the residual add; here all three convolutions
-// are fused as well, so the packed patches never go back to memory):
+// One workgroup owns a run of consecutive entries of the active-patch index list (at most
+// PPW patches at a time) and runs the whole block for them without leaving the CU (Sec. 3.4
+// / App. B.1: gather fused into the dynamic convolution, scatter fused into the residual
+// add; here the three convolutions are fused as well, so packed patches never go back to
+// memory):
 //
-//   phase 0  decode the cell ids into pixel indices of the (S+2)x(S+2) windows
-//   phase 1  conv1: stream the gathered window rows of x through LDS in KC-channel
-//            chunks (double buffered), y1 = ReLU(W1 x + b1) -> LDS, 0 outside the image
-//   phase 2  conv2: implicit GEMM over the 9 taps reading y1 rows by window offset -> y2 LDS
-//   phase 3  conv3 + b3 + residual x, rounded once, stored at the patch's position
+//   phase 0  decode the cell ids; collect the pixels of all (S+2)x(S+2) windows into a set
+//            (LDS hash table): a pixel shared by the windows of neighbouring patches gets
+//            ONE row, pixels outside the image get none -- the overlapping neighbour area
+//            of Sec. 3.4 is loaded and convolved once per workgroup, not once per patch
+//   phase 1  conv1 over the U unique rows: x rows stream through LDS in KC-channel chunks
+//            (double buffered), y1 = ReLU(W1 x + b1) -> LDS
+//   phase 2  conv2: implicit GEMM over the 9 taps, y1 rows looked up per window position
+//            (an all-zero row stands for "outside the image") -> y2 in LDS
+//   phase 3  conv3 + b3 + residual x, rounded once, stored at the patch's own pixels
 //
-// Every GEMM is computed transposed, D[channel][pixel] = W[channel][k] * act[pixel][k],
-// with v_mfma_f32_16x16x32_bf16: the weight fragment (A operand) comes straight from
-// global/L2 in the natural [out][in] layout (8 consecutive k per lane = one 16-byte load),
-// the activation fragment (B operand) from LDS.  In the result a lane holds 4 consecutive
-// rows = channels; the rows of the NB tiles of a pass are interleaved so that a lane ends
-// up with 4*NB consecutive channels of one pixel, which makes the epilogues 8..32-byte
-// vector accesses.  Waves are arranged WR x WC (pixel-blocks x channel-blocks) per phase.
+// Every GEMM is computed transposed, D[channel][pixel] = W[channel][k] * act[pixel][k], with
+// v_mfma_f32_16x16x32_bf16.  The weight fragment (A operand) is read straight from global
+// memory / L2, from a buffer that pack_weights_kernel has laid out fragment by fragment in
+// the order the waves consume them; the activation fragment (B operand) comes from LDS.
+// In the result a lane holds 4 consecutive rows = channels; the rows of the NB tiles of a
+// pass are interleaved so that a lane ends up with 4*NB consecutive channels of one pixel.
+// Waves are arranged WR x WC (pixel-blocks x channel-blocks) per phase.
 #include "common.hpp"
 
 namespace lasnet {
 namespace {
+
+#ifdef LASNET_PHASE_CLOCKS
+__device__ long long g_phase_clk[6 * 2048];
+#define PHASE_MARK(i)                                                            \
+  do {                                                                           \
+    if (threadIdx.x == 0 && blockIdx.x < 2048) g_phase_clk[blockIdx.x * 6 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define PHASE_MARK(i) do { } while (0)
+#endif
 
 __device__ inline floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -29,51 +44,85 @@ __device__ inline floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
 
 constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
+constexpr int pow2_at_least(int v) { int p = 1; while (p < v) p *= 2; return p; }
 
-template <int C_, int M_, int S_, int PPW_, int NW_, int KC_, int WR1_, int WC1_, int WR2_,
-          int WC2_, int GS2_, int WR3_, int WC3_, int NB3_, int GS3_>
+// C, M, S: block shape.  PPW: patches per batch (max).  R1MAX: rows of y1 kept in LDS (unique
+// window pixels of a batch; a batch is cut short if it would need more).  KC: channels of x
+// per staged chunk.  WRi x WCi: wave grid of conv i.  GSi: k-steps per weight prefetch group.
+// NB3: channel tiles per conv3 pass.
+template <int C_, int M_, int S_, int PPW_, int R1MAX_, int NW_, int KC_, int WR1_, int WC1_,
+          int WR2_, int WC2_, int GS2_, int WR3_, int WC3_, int NB3_, int GS3_>
 struct Cfg {
   static constexpr int C = C_, M = M_, S = S_, PPW = PPW_, NW = NW_, KC = KC_;
   static constexpr int NT = NW * 64;
   static constexpr int T = S + 2, WW = T * T;
-  static constexpr int R1 = PPW * WW, R1B = cdiv(R1, 16), R1P = R1B * 16;
+  static constexpr int R1MAX = R1MAX_, R1B = R1MAX / 16;
+  static constexpr int ZROW = R1MAX;                   // index of the all-zero y1 row
   static constexpr int R2 = PPW * S * S, R2B = cdiv(R2, 16), R2P = R2B * 16;
-  static constexpr int LDX = KC + 8, LDY = M + 8;      // +16 bytes: rows land in distinct banks
+  // LDS rows have power-of-two pitch and their 16-byte chunks are XOR-swizzled (see swz()):
+  // measured on gfx950, ds_read_b128 then runs at ~6 clk per wave against ~9 with a padded
+  // pitch.
+  static constexpr int LDX = KC, LDY = M < 128 ? 128 : M;
+  static constexpr int XMASK = KC / 8 - 1;
   static constexpr int WR1 = WR1_, WC1 = WC1_, NBW1 = M / 16 / WC1, RBW1 = cdiv(R1B, WR1);
   static constexpr int WR2 = WR2_, WC2 = WC2_, NBW2 = M / 16 / WC2, RBW2 = cdiv(R2B, WR2);
   static constexpr int GS2 = GS2_;
   static constexpr int WR3 = WR3_, WC3 = WC3_, NBT3 = C / 16 / WC3, NB3 = NB3_, RBW3 = cdiv(R2B, WR3);
   static constexpr int GS3 = GS3_;
   static constexpr int MS = M / 32;                    // k-steps over the mid channels
-  static constexpr int OFF_Y1 = ((R1P + R2P) * 4 + 15) / 16 * 16;
-  static constexpr int Y1_BYTES = R1P * LDY * 2;
+  static constexpr int HT = pow2_at_least(2 * R1MAX);  // hash table slots
+  // LDS map (bytes)
+  static constexpr int OFF_HKEY = 0;                            // int  [HT]     pixel+1 or 0
+  static constexpr int OFF_HVAL = OFF_HKEY + HT * 4;            // short[HT]     row of that pixel
+  static constexpr int OFF_WINROW = OFF_HVAL + HT * 2;          // short[PPW*WW] row of each window position
+  static constexpr int OFF_ROWPIX = (OFF_WINROW + PPW * WW * 2 + 15) / 16 * 16;  // int[R1MAX]
+  static constexpr int OFF_PIXQ = OFF_ROWPIX + R1MAX * 4;       // int  [R2P]
+  static constexpr int OFF_MISC = OFF_PIXQ + R2P * 4;           // int  [4]
+  static constexpr int OFF_Y1 = (OFF_MISC + 16 + 15) / 16 * 16;
+  static constexpr int Y1_BYTES = (R1MAX + 1) * LDY * 2;
   static constexpr int OFF_XS = OFF_Y1 + Y1_BYTES;
-  static constexpr int XS_BYTES = 2 * R1P * LDX * 2;
+  static constexpr int XS_BYTES = 2 * R1MAX * LDX * 2;
   static constexpr int Y2_BYTES = R2P * LDY * 2;
   static constexpr int LDS_BYTES = OFF_XS + cmax(XS_BYTES, Y2_BYTES);
+  static constexpr size_t PACKED_ELEMS = (size_t)M * C * 2 + 9 * (size_t)M * M;
+  static_assert(R1MAX % 16 == 0 && R1MAX >= WW && R1MAX < 32767, "y1 rows");
+  static_assert(HT > PPW * WW, "the hash table always keeps an empty slot, so probing ends");
   static_assert(WR1 * WC1 == NW && WR2 * WC2 == NW && WR3 * WC3 == NW, "wave grid");
   static_assert(M % (16 * WC1) == 0 && M % (16 * WC2) == 0 && C % (16 * WC3) == 0, "channel split");
   static_assert(NBT3 % NB3 == 0, "conv3 passes");
   static_assert(C % KC == 0 && KC % 32 == 0 && M % 32 == 0, "k steps");
+  static_assert((KC & (KC - 1)) == 0 && KC >= 64 && KC <= 128, "x chunk pitch");
   static_assert(MS % GS2 == 0 && MS % GS3 == 0, "weight groups stay inside one tap");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
+// Element offset of 16-byte chunk `chunk` in an LDS row of pitch `ld` elements whose chunks
+// are XOR-swizzled with `key` (low 4 bits of the chunk index at most).
+__device__ inline int swz(int row, int ld, int chunk, int key, int mask = 15) {
+  return row * ld + ((chunk ^ (key & mask)) << 3);
+}
+
 // Channel held by A-operand row i (0..15) of tile j when NB tiles are interleaved.
-__device__ inline int arow_channel(int base, int nb, int j, int i) {
+__host__ __device__ inline int arow_channel(int base, int nb, int j, int i) {
   return base + (i >> 2) * (4 * nb) + j * 4 + (i & 3);
 }
 
+__device__ inline unsigned hash_pix(int pix) { return ((unsigned)pix * 2654435761u) >> 12; }
+
 template <class K>
 __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
-    Geom g, const __bf16* __restrict__ x, const int32_t* __restrict__ idx,
+    Geom g, int tile_slots, const __bf16* __restrict__ x, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ count, const __bf16* __restrict__ W1,
     const float* __restrict__ b1, const __bf16* __restrict__ W2, const float* __restrict__ b2,
     const __bf16* __restrict__ W3, const float* __restrict__ b3, __bf16* __restrict__ out,
     int post_relu) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  int* rowpix = reinterpret_cast<int*>(smem);              // [R1P] pixel of conv1 row or -1
-  int* pixq = rowpix + K::R1P;                             // [R2P] pixel of output row or -1
+  int* hkey = reinterpret_cast<int*>(smem + K::OFF_HKEY);
+  short* hval = reinterpret_cast<short*>(smem + K::OFF_HVAL);
+  short* winrow = reinterpret_cast<short*>(smem + K::OFF_WINROW);
+  int* rowpix = reinterpret_cast<int*>(smem + K::OFF_ROWPIX);
+  int* pixq = reinterpret_cast<int*>(smem + K::OFF_PIXQ);
+  int* misc = reinterpret_cast<int*>(smem + K::OFF_MISC);      // [0] = number of unique rows
   __bf16* y1s = reinterpret_cast<__bf16*>(smem + K::OFF_Y1);
   __bf16* xs = reinterpret_cast<__bf16*>(smem + K::OFF_XS);
   __bf16* y2s = xs;                                        // xs is dead once conv1 is done
@@ -81,320 +130,455 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
   constexpr int C = K::C, M = K::M, S = K::S, T = K::T, WW = K::WW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
-  const int nact = idx ? min(*count, g.P) : g.P;
-  const int first = blockIdx.x * K::PPW;
-  if (first >= nact) return;                               // uniform over the workgroup
 
-  // ---------------------------------------------------------------- phase 0
-  for (int r = tid; r < K::R1P; r += K::NT) {
-    int pix = -1;
-    if (r < K::R1) {
-      const int slot = r / WW, wp = r - slot * WW;
-      const int e = first + slot;
-      if (e < nact) {
-        const int cell = idx ? idx[e] : e;
+  // ---- which entries of the index list are this workgroup's ------------------------------
+  // The list is cut into `nt` near-equal runs, nt = the number of PPW-sized tiles rounded up
+  // to a multiple of `tile_slots` (workgroups the chip holds at once), so that every round
+  // of workgroups is full whatever the count turns out to be.
+  const int nact = idx ? min(*count, g.P) : g.P;
+  if (nact <= 0) return;
+  int nt = (nact + K::PPW - 1) / K::PPW;
+  nt = (nt + tile_slots - 1) / tile_slots * tile_slots;
+  nt = min(min(nt, (int)gridDim.x), nact);
+  if ((int)blockIdx.x >= nt) return;                       // uniform over the workgroup
+  const int tb = (int)(((long long)blockIdx.x * nact) / nt);
+  const int te = (int)(((long long)(blockIdx.x + 1) * nact) / nt);
+  PHASE_MARK(0);
+
+  // the all-zero y1 row
+  for (int i = tid; i < K::LDY / 8; i += K::NT)
+    *reinterpret_cast<uint4*>(y1s + K::ZROW * K::LDY + i * 8) = uint4{0, 0, 0, 0};
+
+  for (int e0 = tb; e0 < te;) {
+    // ---------------------------------------------------------------- phase 0
+    int npb = min(te - e0, K::PPW);                        // patches in this batch
+    int U;                                                 // unique window pixels = y1 rows
+    for (;;) {
+      for (int i = tid; i < K::HT; i += K::NT) hkey[i] = 0;
+      if (tid == 0) misc[0] = 0;
+      __syncthreads();
+      // (a) every in-image window pixel claims a hash slot
+      for (int t = tid; t < npb * WW; t += K::NT) {
+        const int slot = t / WW, wp = t - slot * WW;
+        const int cell = idx ? idx[e0 + slot] : e0 + slot;
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
         const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
-        if (h >= 0 && h < g.H && w >= 0 && w < g.W) pix = (n * g.H + h) * g.W + w;
+        if (h >= 0 && h < g.H && w >= 0 && w < g.W) {
+          const int key = (n * g.H + h) * g.W + w + 1;
+          unsigned s = hash_pix(key) & (K::HT - 1);
+          for (;;) {
+            const int old = atomicCAS(&hkey[s], 0, key);
+            if (old == 0 || old == key) break;
+            s = (s + 1) & (K::HT - 1);
+          }
+        }
       }
+      __syncthreads();
+      // (b) occupied slots take row numbers
+      for (int i = tid; i < K::HT; i += K::NT) {
+        const int key = hkey[i];
+        if (key != 0) {
+          const int row = atomicAdd(&misc[0], 1);
+          hval[i] = (short)row;
+          if (row < K::R1MAX) rowpix[row] = key - 1;
+        }
+      }
+      __syncthreads();
+      U = misc[0];
+      if (U <= K::R1MAX) break;
+      // too many distinct pixels for the y1 buffer: retry with fewer patches (WW <= R1MAX, so
+      // one patch always fits)
+      npb = max(1, min(npb - 1, npb * K::R1MAX / U));
+      __syncthreads();
     }
-    rowpix[r] = pix;
-  }
-  for (int q = tid; q < K::R2P; q += K::NT) {
-    int pix = -1;
-    if (q < K::R2) {
-      const int slot = q / (S * S), r = q - slot * (S * S);
-      const int e = first + slot;
-      if (e < nact) {
-        const int cell = idx ? idx[e] : e;
+    const int nblk1 = (U + 15) >> 4;
+    const int nq = npb * S * S, nblk2 = (nq + 15) >> 4;
+    // (c) row of every window position; pixel of every output row
+    for (int t = tid; t < npb * WW; t += K::NT) {
+      const int slot = t / WW, wp = t - slot * WW;
+      const int cell = idx ? idx[e0 + slot] : e0 + slot;
+      const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
+      const int gy = rem / g.GW, gx = rem - gy * g.GW;
+      const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
+      int row = K::ZROW;
+      if (h >= 0 && h < g.H && w >= 0 && w < g.W) {
+        const int key = (n * g.H + h) * g.W + w + 1;
+        unsigned s = hash_pix(key) & (K::HT - 1);
+        while (hkey[s] != key) s = (s + 1) & (K::HT - 1);
+        row = hval[s];
+      }
+      winrow[t] = (short)row;
+    }
+    for (int r = U + tid; r < nblk1 * 16; r += K::NT) rowpix[r] = -1;
+    for (int q = tid; q < K::R2P; q += K::NT) {
+      int pix = -1;
+      if (q < nq) {
+        const int slot = q / (S * S), r = q - slot * (S * S);
+        const int cell = idx ? idx[e0 + slot] : e0 + slot;
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
         pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
       }
+      pixq[q] = pix;
     }
-    pixq[q] = pix;
-  }
-  __syncthreads();
-
-  // ---------------------------------------------------------------- phase 1: conv1
-  {
-    constexpr int RBW = K::RBW1, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
-    constexpr int SEGS = K::KC / 8, NPIECE = K::R1P * SEGS, NP = cdiv(NPIECE, K::NT);
-    const int wr = wave / K::WC1, wc = wave % K::WC1;
-    floatx4 acc[RBW][NBW];
-#pragma unroll
-    for (int i = 0; i < RBW; ++i)
-#pragma unroll
-      for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const __bf16* wrow[NBW];
-#pragma unroll
-    for (int j = 0; j < NBW; ++j)
-      wrow[j] = W1 + (size_t)arow_channel(wc * NBW * 16, NBW, j, l16) * C + 8 * lg;
-    const __bf16* xsrc[NP];
-    int xdst[NP];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int piece = tid + p * K::NT;
-      xsrc[p] = nullptr;
-      xdst[p] = -1;
-      if (piece < NPIECE) {
-        const int row = piece / SEGS, seg = piece - row * SEGS;
-        const int pix = rowpix[row];
-        if (pix >= 0) xsrc[p] = x + (size_t)pix * C + seg * 8;
-        xdst[p] = row * K::LDX + seg * 8;
-      }
-    }
-    uint4 xr[NP];
-    bf16x8 wa[KS][NBW], wb[KS][NBW];
-    auto gload = [&](int ch) {
-#pragma unroll
-      for (int p = 0; p < NP; ++p)
-        xr[p] = xsrc[p] ? *reinterpret_cast<const uint4*>(xsrc[p] + ch * K::KC) : uint4{0, 0, 0, 0};
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-      for (int p = 0; p < NP; ++p)
-        if (xdst[p] >= 0) *reinterpret_cast<uint4*>(xs + buf * (K::R1P * K::LDX) + xdst[p]) = xr[p];
-    };
-    auto wload = [&](bf16x8(&w)[KS][NBW], int ch) {
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int j = 0; j < NBW; ++j)
-          w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + ch * K::KC + s * 32);
-    };
-    gload(0);
-    wload(wa, 0);
-    sstore(0);
     __syncthreads();
-    for (int ch = 0; ch < NCH; ++ch) {
-      const bool more = ch + 1 < NCH;
-      if (more) {
-        gload(ch + 1);
-        wload(wb, ch + 1);
-      }
-      const __bf16* xb = xs + (ch & 1) * (K::R1P * K::LDX);
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int i = 0; i < RBW; ++i) {
-          const int rb = wr + K::WR1 * i;
-          if (rb < K::R1B) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8*>(xb + (rb * 16 + l16) * K::LDX + s * 32 + 8 * lg);
-#pragma unroll
-            for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
-          }
-        }
-      if (more) {
-        sstore((ch + 1) & 1);
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
-      }
-      __syncthreads();
-    }
-    // epilogue: + b1, ReLU, force 0 outside the image / on unused rows, round to bf16
-    const int chb = wc * NBW * 16 + lg * 4 * NBW;
-#pragma unroll
-    for (int i = 0; i < RBW; ++i) {
-      const int rb = wr + K::WR1 * i;
-      if (rb < K::R1B) {
-        const int row = rb * 16 + l16;
-        const bool valid = rowpix[row] >= 0;
-#pragma unroll
-        for (int j = 0; j < NBW; ++j) {
-          bf16x4 o;
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const float a = fmaxf(acc[i][j][v] + b1[chb + j * 4 + v], 0.f);
-            o[v] = (__bf16)(valid ? a : 0.f);
-          }
-          *reinterpret_cast<bf16x4*>(y1s + row * K::LDY + chb + j * 4) = o;
-        }
-      }
-    }
-  }
-  __syncthreads();
+    PHASE_MARK(1);
 
-  // ---------------------------------------------------------------- phase 2: conv2 (3x3)
-  {
-    constexpr int RBW = K::RBW2, NBW = K::NBW2, GS = K::GS2, MS = K::MS;
-    constexpr int GPT = MS / GS, NG = 9 * GPT;             // groups per tap, groups in all
-    const int wr = wave / K::WC2, wc = wave % K::WC2;
-    floatx4 acc[RBW][NBW];
-#pragma unroll
-    for (int i = 0; i < RBW; ++i)
-#pragma unroll
-      for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    int brow[RBW];                                         // window row of tap (0,0)
-#pragma unroll
-    for (int i = 0; i < RBW; ++i) {
-      const int q = (wr + K::WR2 * i) * 16 + l16;
-      brow[i] = 0;
-      if (q < K::R2) {
-        const int slot = q / (S * S), r = q - slot * (S * S);
-        brow[i] = slot * WW + (r / S) * T + r % S;
-      }
-    }
-    const __bf16* wrow[NBW];
-#pragma unroll
-    for (int j = 0; j < NBW; ++j)
-      wrow[j] = W2 + (size_t)arow_channel(wc * NBW * 16, NBW, j, l16) * (9 * M) + 8 * lg;
-    bf16x8 wa[GS][NBW], wb[GS][NBW];
-    auto wload = [&](bf16x8(&w)[GS][NBW], int grp) {
-#pragma unroll
-      for (int s = 0; s < GS; ++s)
-#pragma unroll
-        for (int j = 0; j < NBW; ++j)
-          w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * 32);
-    };
-    wload(wa, 0);
-    for (int grp = 0; grp < NG; ++grp) {
-      if (grp + 1 < NG) wload(wb, grp + 1);
-      const int tap = grp / GPT, m0 = (grp - tap * GPT) * GS * 32;
-      const int toff = (tap / 3) * T + tap % 3;
-#pragma unroll
-      for (int s = 0; s < GS; ++s)
-#pragma unroll
-        for (int i = 0; i < RBW; ++i) {
-          if (wr + K::WR2 * i < K::R2B) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                y1s + (brow[i] + toff) * K::LDY + m0 + s * 32 + 8 * lg);
-#pragma unroll
-            for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
-          }
-        }
-      if (grp + 1 < NG) {
-#pragma unroll
-        for (int s = 0; s < GS; ++s)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
-      }
-    }
-    const int chb = wc * NBW * 16 + lg * 4 * NBW;
-#pragma unroll
-    for (int i = 0; i < RBW; ++i) {
-      const int rb = wr + K::WR2 * i;
-      if (rb < K::R2B) {
-        const int q = rb * 16 + l16;
-#pragma unroll
-        for (int j = 0; j < NBW; ++j) {
-          bf16x4 o;
-#pragma unroll
-          for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b2[chb + j * 4 + v], 0.f);
-          *reinterpret_cast<bf16x4*>(y2s + q * K::LDY + chb + j * 4) = o;
-        }
-      }
-    }
-  }
-  __syncthreads();
-
-  // ---------------------------------------------------------------- phase 3: conv3 + scatter-add
-  {
-    constexpr int RBW = K::RBW3, NB = K::NB3, GS = K::GS3, MS = K::MS, NG = MS / GS;
-    constexpr int NPASS = K::NBT3 / NB;
-    const int wr = wave / K::WC3, wc = wave % K::WC3;
-    int pq[RBW];
-#pragma unroll
-    for (int i = 0; i < RBW; ++i) {
-      const int rb = wr + K::WR3 * i;
-      pq[i] = rb < K::R2B ? pixq[rb * 16 + l16] : -1;
-    }
-    for (int pass = 0; pass < NPASS; ++pass) {
-      const int cb0 = (wc * K::NBT3 + pass * NB) * 16;     // first channel of this pass
-      floatx4 acc[RBW][NB];
+    // ---------------------------------------------------------------- phase 1: conv1
+    {
+      constexpr int RBW = K::RBW1, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
+      constexpr int SEGS = K::KC / 8, NP = cdiv(K::R1MAX * SEGS, K::NT);
+      const int npiece = nblk1 * 16 * SEGS;
+      const int wr = wave / K::WC1, wc = wave % K::WC1;
+      floatx4 acc[RBW][NBW];
 #pragma unroll
       for (int i = 0; i < RBW; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-      const __bf16* wrow[NB];
+        for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+      const __bf16* wrow[NBW];
 #pragma unroll
-      for (int j = 0; j < NB; ++j)
-        wrow[j] = W3 + (size_t)arow_channel(cb0, NB, j, l16) * M + 8 * lg;
-      bf16x8 wa[GS][NB], wb[GS][NB];
-      auto wload = [&](bf16x8(&w)[GS][NB], int grp) {
+      for (int j = 0; j < NBW; ++j) wrow[j] = W1 + (wc * NBW + j) * 512 + lane * 8;
+      const __bf16* xsrc[NP];
+      int xdst[NP];
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const int piece = tid + p * K::NT;
+        xsrc[p] = nullptr;
+        xdst[p] = -1;
+        if (piece < npiece) {
+          const int row = piece / SEGS, seg = piece - row * SEGS;
+          const int pix = rowpix[row];
+          if (pix >= 0) xsrc[p] = x + (size_t)pix * C + seg * 8;
+          xdst[p] = swz(row, K::LDX, seg, row, K::XMASK);
+        }
+      }
+      uint4 xr[NP];
+      bf16x8 wa[KS][NBW], wb[KS][NBW];
+      auto gload = [&](int ch) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+          xr[p] = xsrc[p] ? *reinterpret_cast<const uint4*>(xsrc[p] + ch * K::KC) : uint4{0, 0, 0, 0};
+      };
+      auto sstore = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+          if (xdst[p] >= 0) *reinterpret_cast<uint4*>(xs + buf * (K::R1MAX * K::LDX) + xdst[p]) = xr[p];
+      };
+      auto wload = [&](bf16x8(&w)[KS][NBW], int ch) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+          for (int j = 0; j < NBW; ++j)
+            w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (ch * KS + s) * (M * 32));
+      };
+      gload(0);
+      wload(wa, 0);
+      sstore(0);
+      __syncthreads();
+      for (int ch = 0; ch < NCH; ++ch) {
+        const bool more = ch + 1 < NCH;
+        if (more) {
+          gload(ch + 1);
+          wload(wb, ch + 1);
+        }
+        const __bf16* xb = xs + (ch & 1) * (K::R1MAX * K::LDX);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+          for (int i = 0; i < RBW; ++i) {
+            const int rb = wr + K::WR1 * i;
+            if (rb < nblk1) {
+              const int row = rb * 16 + l16;
+              const bf16x8 b = *reinterpret_cast<const bf16x8*>(xb + swz(row, K::LDX, s * 4 + lg, row, K::XMASK));
+#pragma unroll
+              for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
+            }
+          }
+        if (more) {
+          sstore((ch + 1) & 1);
+#pragma unroll
+          for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
+        }
+        __syncthreads();
+      }
+      // epilogue: + b1, ReLU, round to bf16
+      const int chb = wc * NBW * 16 + lg * 4 * NBW;
+#pragma unroll
+      for (int i = 0; i < RBW; ++i) {
+        const int rb = wr + K::WR1 * i;
+        if (rb < nblk1) {
+          const int row = rb * 16 + l16;
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            bf16x4 o;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b1[chb + j * 4 + v], 0.f);
+            const int c = chb + j * 4;
+            *reinterpret_cast<bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row) + (c & 7)) = o;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    PHASE_MARK(2);
+
+    // ---------------------------------------------------------------- phase 2: conv2 (3x3)
+    {
+      constexpr int RBW = K::RBW2, NBW = K::NBW2, GS = K::GS2, MS = K::MS;
+      constexpr int GPT = MS / GS, NG = 9 * GPT;           // groups per tap, groups in all
+      const int wr = wave / K::WC2, wc = wave % K::WC2;
+      floatx4 acc[RBW][NBW];
+#pragma unroll
+      for (int i = 0; i < RBW; ++i)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+      int wpos[RBW];                                       // window position of tap (0,0)
+#pragma unroll
+      for (int i = 0; i < RBW; ++i) {
+        const int q = (wr + K::WR2 * i) * 16 + l16;
+        wpos[i] = -1;
+        if (q < nq) {
+          const int slot = q / (S * S), r = q - slot * (S * S);
+          wpos[i] = slot * WW + (r / S) * T + r % S;
+        }
+      }
+      const __bf16* wrow[NBW];
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) wrow[j] = W2 + (wc * NBW + j) * 512 + lane * 8;
+      bf16x8 wa[GS][NBW], wb[GS][NBW];
+      auto wload = [&](bf16x8(&w)[GS][NBW], int grp) {
 #pragma unroll
         for (int s = 0; s < GS; ++s)
 #pragma unroll
-          for (int j = 0; j < NB; ++j)
-            w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * 32);
+          for (int j = 0; j < NBW; ++j)
+            w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * (M * 32));
       };
       wload(wa, 0);
+      int brow[RBW];
 #pragma unroll
+      for (int i = 0; i < RBW; ++i) brow[i] = K::ZROW;
       for (int grp = 0; grp < NG; ++grp) {
         if (grp + 1 < NG) wload(wb, grp + 1);
+        const int tap = grp / GPT, m0 = (grp - tap * GPT) * GS * 32;
+        if (grp == tap * GPT) {                            // new tap: look the rows up
+          const int toff = (tap / 3) * T + tap % 3;
+#pragma unroll
+          for (int i = 0; i < RBW; ++i) brow[i] = wpos[i] >= 0 ? winrow[wpos[i] + toff] : K::ZROW;
+        }
 #pragma unroll
         for (int s = 0; s < GS; ++s)
 #pragma unroll
           for (int i = 0; i < RBW; ++i) {
-            const int rb = wr + K::WR3 * i;
-            if (rb < K::R2B) {
+            if (wr + K::WR2 * i < nblk2) {
               const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                  y2s + (rb * 16 + l16) * K::LDY + (grp * GS + s) * 32 + 8 * lg);
+                  y1s + swz(brow[i], K::LDY, (m0 >> 3) + s * 4 + lg, brow[i]));
 #pragma unroll
-              for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
+              for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
             }
           }
         if (grp + 1 < NG) {
 #pragma unroll
           for (int s = 0; s < GS; ++s)
 #pragma unroll
-            for (int j = 0; j < NB; ++j) wa[s][j] = wb[s][j];
+            for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
         }
       }
-      // epilogue: residual add in fp32, one rounding, store at the patch's own pixels
-      const int chb = cb0 + lg * 4 * NB;
+      const int chb = wc * NBW * 16 + lg * 4 * NBW;
 #pragma unroll
       for (int i = 0; i < RBW; ++i) {
-        if (pq[i] >= 0) {
-          const size_t off = (size_t)pq[i] * C + chb;
+        const int rb = wr + K::WR2 * i;
+        if (rb < nblk2) {
+          const int q = rb * 16 + l16;
 #pragma unroll
-          for (int j = 0; j < NB; ++j) {
-            const bf16x4 xv = *reinterpret_cast<const bf16x4*>(x + off + j * 4);
+          for (int j = 0; j < NBW; ++j) {
             bf16x4 o;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              float r = (float)xv[v] + (acc[i][j][v] + b3[chb + j * 4 + v]);
-              if (post_relu) r = fmaxf(r, 0.f);
-              o[v] = (__bf16)r;
-            }
-            *reinterpret_cast<bf16x4*>(out + off + j * 4) = o;
+            for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b2[chb + j * 4 + v], 0.f);
+            const int c = chb + j * 4;
+            *reinterpret_cast<bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q) + (c & 7)) = o;
           }
         }
       }
     }
+    __syncthreads();
+    PHASE_MARK(3);
+
+    // ---------------------------------------------------------------- phase 3: conv3 + scatter-add
+    {
+      constexpr int RBW = K::RBW3, NB = K::NB3, GS = K::GS3, MS = K::MS, NG = MS / GS;
+      constexpr int NPASS = K::NBT3 / NB;
+      const int wr = wave / K::WC3, wc = wave % K::WC3;
+      int pq[RBW];
+#pragma unroll
+      for (int i = 0; i < RBW; ++i) {
+        const int rb = wr + K::WR3 * i;
+        pq[i] = rb < nblk2 ? pixq[rb * 16 + l16] : -1;
+      }
+      for (int pass = 0; pass < NPASS; ++pass) {
+        const int cb0 = (wc * K::NBT3 + pass * NB) * 16;   // first channel of this pass
+        floatx4 acc[RBW][NB];
+#pragma unroll
+        for (int i = 0; i < RBW; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const __bf16* wrow[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          wrow[j] = W3 + (((wc * NPASS + pass) * MS) * NB + j) * 512 + lane * 8;
+        bf16x8 wa[GS][NB], wb[GS][NB];
+        auto wload = [&](bf16x8(&w)[GS][NB], int grp) {
+#pragma unroll
+          for (int s = 0; s < GS; ++s)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+              w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * (NB * 512));
+        };
+        wload(wa, 0);
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) {
+          if (grp + 1 < NG) wload(wb, grp + 1);
+#pragma unroll
+          for (int s = 0; s < GS; ++s)
+#pragma unroll
+            for (int i = 0; i < RBW; ++i) {
+              const int rb = wr + K::WR3 * i;
+              if (rb < nblk2) {
+                const int q = rb * 16 + l16;
+                const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+                    y2s + swz(q, K::LDY, (grp * GS + s) * 4 + lg, q));
+#pragma unroll
+                for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
+              }
+            }
+          if (grp + 1 < NG) {
+#pragma unroll
+            for (int s = 0; s < GS; ++s)
+#pragma unroll
+              for (int j = 0; j < NB; ++j) wa[s][j] = wb[s][j];
+          }
+        }
+        // epilogue: residual add in fp32, one rounding, store at the patch's own pixels
+        const int chb = cb0 + lg * 4 * NB;
+#pragma unroll
+        for (int i = 0; i < RBW; ++i) {
+          if (pq[i] >= 0) {
+            const size_t off = (size_t)pq[i] * C + chb;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+              const bf16x4 xv = *reinterpret_cast<const bf16x4*>(x + off + j * 4);
+              bf16x4 o;
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                float r = (float)xv[v] + (acc[i][j][v] + b3[chb + j * 4 + v]);
+                if (post_relu) r = fmaxf(r, 0.f);
+                o[v] = (__bf16)r;
+              }
+              *reinterpret_cast<bf16x4*>(out + off + j * 4) = o;
+            }
+          }
+        }
+      }
+    }
+    e0 += npb;
+    if (e0 < te) __syncthreads();                          // LDS is reused by the next batch
   }
+  PHASE_MARK(4);
+}
+
+// Rewrites W1|W2|W3 in the order the fused kernel's waves consume them: one 16x32 MFMA
+// A-fragment (64 lanes x 16 bytes) per contiguous KiB, fragments of one k-step next to
+// each other.  A wave's weight stream is then a run of whole cache lines spread over all
+// L2 channels, instead of 64-byte pieces of rows that sit a power of two apart (which
+// measured 2x slower end to end).
+template <class K>
+__global__ __launch_bounds__(256) void pack_weights_kernel(const __bf16* __restrict__ W1,
+                                                           const __bf16* __restrict__ W2,
+                                                           const __bf16* __restrict__ W3,
+                                                           __bf16* __restrict__ packed) {
+  constexpr int C = K::C, M = K::M, MS = K::MS;
+  constexpr int N1 = M * C / 8, N2 = 9 * M * M / 8, N3 = C * M / 8;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= N1 + N2 + N3) return;
+  const int lane = t & 63, l16 = lane & 15, lg = lane >> 4;
+  const __bf16* src;
+  if (t < N1) {
+    const int f = t >> 6, kstep = f / (M / 16), fb = f % (M / 16);
+    const int wc = fb / K::NBW1, j = fb % K::NBW1;
+    src = W1 + (size_t)arow_channel(wc * K::NBW1 * 16, K::NBW1, j, l16) * C + kstep * 32 + 8 * lg;
+  } else if (t < N1 + N2) {
+    const int f = (t - N1) >> 6, kstep = f / (M / 16), fb = f % (M / 16);
+    const int wc = fb / K::NBW2, j = fb % K::NBW2;
+    src = W2 + (size_t)arow_channel(wc * K::NBW2 * 16, K::NBW2, j, l16) * (9 * M) + kstep * 32 + 8 * lg;
+  } else {
+    constexpr int NPASS = K::NBT3 / K::NB3;
+    int f = (t - N1 - N2) >> 6;
+    const int j = f % K::NB3; f /= K::NB3;
+    const int step = f % MS; f /= MS;
+    const int pass = f % NPASS, wc = f / NPASS;
+    src = W3 + (size_t)arow_channel((wc * K::NBT3 + pass * K::NB3) * 16, K::NB3, j, l16) * M + step * 32 + 8 * lg;
+  }
+  *reinterpret_cast<uint4*>(packed + (size_t)t * 8) = *reinterpret_cast<const uint4*>(src);
 }
 
 // ---- instantiations --------------------------------------------------------------
-//            C     M   S PPW NW KC  conv1   conv2+GS   conv3 NB GS
-using K_s3 = Cfg<1024, 256, 2, 8, 8, 64, 2, 4, 1, 8, 4, 1, 8, 4, 2>;   // ResNet-101 stage 3, S=2
-using K_s3s7 = Cfg<1024, 256, 7, 1, 8, 64, 2, 4, 2, 4, 4, 2, 4, 4, 2>; // stage 3, S=7 (also the dense tile)
-using K_s2 = Cfg<512, 128, 4, 4, 8, 64, 2, 4, 2, 4, 4, 2, 4, 4, 2>;    // stage 2, S=4
-using K_s2s7 = Cfg<512, 128, 7, 2, 8, 64, 2, 4, 2, 4, 4, 2, 4, 4, 2>;  // stage 2, S=7 (dense tile)
-using K_s1 = Cfg<256, 64, 8, 1, 8, 64, 4, 2, 4, 2, 2, 2, 4, 4, 2>;     // stage 1, S=8
-using K_s1s4 = Cfg<256, 64, 4, 4, 8, 64, 4, 2, 4, 2, 2, 2, 4, 4, 2>;   // stage 1, S=4 (Table 1 block)
-using K_s1s7 = Cfg<256, 64, 7, 2, 8, 64, 4, 2, 4, 2, 2, 2, 4, 4, 2>;   // stage 1, S=7 (dense tile)
+//             C     M   S PPW R1MAX NW KC  conv1  conv2+GS  conv3 NB GS
+using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // ResNet-101 stage 3, S=2
+using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // stage 3, S=7 (also the dense tile)
+using K_s2 = Cfg<512, 128, 4, 8, 256, 8, 64, 2, 4, 1, 8, 4, 1, 8, 4, 2>;      // stage 2, S=4
+using K_s2s7 = Cfg<512, 128, 7, 2, 176, 8, 64, 2, 4, 1, 8, 4, 1, 8, 4, 2>;    // stage 2, S=7 (dense tile)
+using K_s1 = Cfg<256, 64, 8, 2, 208, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;       // stage 1, S=8
+using K_s1s4 = Cfg<256, 64, 4, 8, 256, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;     // stage 1, S=4 (Table 1 block)
+using K_s1s7 = Cfg<256, 64, 7, 2, 176, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;     // stage 1, S=7 (dense tile)
+
+#define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
+
+int device_cu_count() {
+  static int cus = 0;                        // one kind of device per process
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
 
 template <class K>
 hipError_t launch_one(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
-                      const BlockWeights& w, void* out, bool post_relu, hipStream_t st) {
+                      const void* packed, const float* b1, const float* b2, const float* b3,
+                      void* out, bool post_relu, hipStream_t st) {
   auto k = fused_bneck_kernel<K>;
-  hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     K::LDS_BYTES);
-  if (e != hipSuccess) return e;
-  const int grid = (g.P + K::PPW - 1) / K::PPW;
-  hipLaunchKernelGGL(k, dim3(grid), dim3(K::NT), K::LDS_BYTES, st, g, (const __bf16*)x, idx, count,
-                     (const __bf16*)w.W1, w.b1, (const __bf16*)w.W2, w.b2, (const __bf16*)w.W3,
-                     w.b3, (__bf16*)out, (int)post_relu);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       K::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int slots = device_cu_count() * ((160 * 1024) / K::LDS_BYTES);
+  int grid = (g.P + K::PPW - 1) / K::PPW;
+  grid = (grid + slots - 1) / slots * slots;
+  if (grid > g.P) grid = g.P;
+  const __bf16* p1 = (const __bf16*)packed;
+  const __bf16* p2 = p1 + (size_t)K::M * K::C;
+  const __bf16* p3 = p2 + 9 * (size_t)K::M * K::M;
+  hipLaunchKernelGGL(k, dim3(grid), dim3(K::NT), K::LDS_BYTES, st, g, slots, (const __bf16*)x, idx,
+                     count, p1, b1, p2, b2, p3, b3, (__bf16*)out, (int)post_relu);
   return hipGetLastError();
 }
 
 }  // namespace
 
-#define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
+#ifdef LASNET_PHASE_CLOCKS
+extern "C" __attribute__((visibility("default"))) int lasnet_debug_read_clocks(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase_clk), sizeof(long long) * n);
+}
+#endif
 
 bool mfma_supported(int C, int M, int S) {
 #define X(K) if (C == K::C && M == K::M && S == K::S) return true;
@@ -403,10 +587,32 @@ bool mfma_supported(int C, int M, int S) {
   return false;
 }
 
+size_t mfma_packed_bytes(int C, int M, int S) {
+#define X(K) if (C == K::C && M == K::M && S == K::S) return K::PACKED_ELEMS * 2;
+  LASNET_FOR_EACH_MFMA_CFG(X)
+#undef X
+  return 0;
+}
+
+hipError_t launch_pack(int C, int M, int S, const void* W1, const void* W2, const void* W3,
+                       void* packed, hipStream_t st) {
+#define X(K)                                                                                   \
+  if (C == K::C && M == K::M && S == K::S) {                                                   \
+    hipLaunchKernelGGL(pack_weights_kernel<K>, dim3((unsigned)((K::PACKED_ELEMS / 8 + 255) / 256)), \
+                       dim3(256), 0, st, (const __bf16*)W1, (const __bf16*)W2, (const __bf16*)W3, \
+                       (__bf16*)packed);                                                       \
+    return hipGetLastError();                                                                  \
+  }
+  LASNET_FOR_EACH_MFMA_CFG(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_mfma(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
-                       const BlockWeights& w, void* out, bool post_relu, hipStream_t st) {
+                       const void* packed, const float* b1, const float* b2, const float* b3,
+                       void* out, bool post_relu, hipStream_t st) {
   if (g.P == 0) return hipSuccess;
-#define X(K) if (g.C == K::C && g.M == K::M && g.S == K::S) return launch_one<K>(g, x, idx, count, w, out, post_relu, st);
+#define X(K) if (g.C == K::C && g.M == K::M && g.S == K::S) return launch_one<K>(g, x, idx, count, packed, b1, b2, b3, out, post_relu, st);
   LASNET_FOR_EACH_MFMA_CFG(X)
 #undef X
   return hipErrorInvalidValue;

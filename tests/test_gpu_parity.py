@@ -174,6 +174,40 @@ def test_index_order_does_not_matter_and_direct_lists(structure):
     assert np.array_equal(U.bits(a), U.bits(b))
 
 
+def test_isolated_patches_overflow_the_shared_halo_buffer():
+    """Cells two apart share no neighbour pixels: a 16-patch batch then needs more distinct
+    rows than the kernel keeps, and it has to split the batch (and still be exact)."""
+    cfg = _cfg("stage3_b128", N=3, name="s3_isolated")
+    cells = [n * 49 + gy * 7 + gx for n in range(cfg.N) for gy in (0, 2, 4, 6) for gx in (0, 2, 4, 6)]
+    _run_case(cfg, idx_np=np.array(cells, np.int32), use_masker=False)
+    cfg = _cfg("stage2_b128", N=2, name="s2_isolated")
+    cells = [n * 49 + gy * 7 + gx for n in range(cfg.N) for gy in (1, 3, 5) for gx in (0, 2, 4, 6)]
+    _run_case(cfg, idx_np=np.array(cells, np.int32), use_masker=False)
+
+
+def test_prepacked_weights_entry_point_matches_plain_one():
+    cfg = _cfg("stage3_b128", N=3, name="s3_packed")
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=11)
+    idx = torch.from_numpy(il).cuda()
+    count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
+    a = B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d))
+    packed = B.lasnet_pack_weights(cfg.S, d["W1"], d["W2"], d["W3"])
+    b = torch.full_like(d["x"], 3.0)
+    B.lasnet_sparse_bottleneck_packed(d["x"], idx, count, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out=b)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.bits(a), U.bits(b))
+    mask = np.zeros(cfg.P, np.uint8); mask[il] = 1
+    mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
+    ref = O.sparse_bottleneck(inp.f64["x"], mask, cfg.S, *_oracle_w(inp))
+    up = np.broadcast_to(O.upsample_mask(mask, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(b, ref, d["x"], up, cfg.dtype, cfg.name)
+    # shapes without a matrix-core kernel are refused, not silently served by another path
+    assert B.lib().lasnet_packed_weights_bytes(B.LASNET_BF16, 64, 16, 4) == 0
+    assert B.lib().lasnet_packed_weights_bytes(B.LASNET_F32, 1024, 256, 2) == 0
+
+
 def test_all_active_null_index_list_equals_dense_oracle():
     cfg = _cfg("stage3_b128", N=2, name="s3_null_idx")
     inp = synth.make_block_inputs(cfg)
