@@ -25,6 +25,8 @@
 // Waves are arranged WR x WC (pixel-blocks x channel-blocks) per phase.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace lasnet {
 namespace {
 
@@ -44,31 +46,31 @@ __device__ inline floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
 
 constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
+constexpr int roundup(int a, int b) { return cdiv(a, b) * b; }
 constexpr int pow2_at_least(int v) { int p = 1; while (p < v) p *= 2; return p; }
 
 // C, M, S: block shape.  PPW: patches per batch (max).  R1MAX: rows of y1 kept in LDS (unique
-// window pixels of a batch; a batch is cut short if it would need more).  KC: channels of x
-// per staged chunk.  WRi x WCi: wave grid of conv i.  GSi: k-steps per weight prefetch group.
+// window pixels of a batch; a batch is cut short if it would need more).  NSTG: LDS stages of
+// the x stream (KC channels each; x chunks are in flight NSTG-1 chunks ahead).  WRi x WCi:
+// wave grid of conv i.  RD2/RD3: k-steps of weights a wave keeps in flight in conv2/conv3.
 // NB3: channel tiles per conv3 pass.
-template <int C_, int M_, int S_, int PPW_, int R1MAX_, int NW_, int KC_, int WR1_, int WC1_,
-          int WR2_, int WC2_, int GS2_, int WR3_, int WC3_, int NB3_, int GS3_>
+template <int C_, int M_, int S_, int PPW_, int R1MAX_, int NW_, int KC_, int NSTG_, int WR1_,
+          int WC1_, int WR2_, int WC2_, int RD2_, int WR3_, int WC3_, int NB3_, int RD3_>
 struct Cfg {
-  static constexpr int C = C_, M = M_, S = S_, PPW = PPW_, NW = NW_, KC = KC_;
+  static constexpr int C = C_, M = M_, S = S_, PPW = PPW_, NW = NW_, KC = KC_, NSTG = NSTG_;
   static constexpr int NT = NW * 64;
   static constexpr int T = S + 2, WW = T * T;
   static constexpr int R1MAX = R1MAX_, R1B = R1MAX / 16;
   static constexpr int ZROW = R1MAX;                   // index of the all-zero y1 row
-  static constexpr int R2 = PPW * S * S, R2B = cdiv(R2, 16), R2P = R2B * 16;
+  static constexpr int WR1 = WR1_, WC1 = WC1_, NBW1 = M / 16 / WC1;
+  static constexpr int WR2 = WR2_, WC2 = WC2_, NBW2 = M / 16 / WC2, RD2 = RD2_;
+  static constexpr int WR3 = WR3_, WC3 = WC3_, NBT3 = C / 16 / WC3, NB3 = NB3_, RD3 = RD3_;
+  static constexpr int R2 = PPW * S * S;
+  static constexpr int R2B = roundup(cdiv(R2, 16), cmax(WR2, WR3)), R2P = R2B * 16;
   // LDS rows have power-of-two pitch and their 16-byte chunks are XOR-swizzled (see swz()):
-  // measured on gfx950, ds_read_b128 then runs at ~6 clk per wave against ~9 with a padded
-  // pitch.
+  // measured on gfx950, ds_read_b128 then runs at ~6 clk per wave against ~9 with a padded pitch.
   static constexpr int LDX = KC, LDY = M < 128 ? 128 : M;
   static constexpr int XMASK = KC / 8 - 1;
-  static constexpr int WR1 = WR1_, WC1 = WC1_, NBW1 = M / 16 / WC1, RBW1 = cdiv(R1B, WR1);
-  static constexpr int WR2 = WR2_, WC2 = WC2_, NBW2 = M / 16 / WC2, RBW2 = cdiv(R2B, WR2);
-  static constexpr int GS2 = GS2_;
-  static constexpr int WR3 = WR3_, WC3 = WC3_, NBT3 = C / 16 / WC3, NB3 = NB3_, RBW3 = cdiv(R2B, WR3);
-  static constexpr int GS3 = GS3_;
   static constexpr int MS = M / 32;                    // k-steps over the mid channels
   static constexpr int HT = pow2_at_least(2 * R1MAX);  // hash table slots
   // LDS map (bytes)
@@ -81,18 +83,20 @@ struct Cfg {
   static constexpr int OFF_Y1 = (OFF_MISC + 16 + 15) / 16 * 16;
   static constexpr int Y1_BYTES = (R1MAX + 1) * LDY * 2;
   static constexpr int OFF_XS = OFF_Y1 + Y1_BYTES;
-  static constexpr int XS_BYTES = 2 * R1MAX * LDX * 2;
+  static constexpr int STAGE_ELEMS = R1MAX * LDX;
+  static constexpr int XS_BYTES = NSTG * STAGE_ELEMS * 2 + 1024;  // + 1 KiB that padding loads land in
   static constexpr int Y2_BYTES = R2P * LDY * 2;
   static constexpr int LDS_BYTES = OFF_XS + cmax(XS_BYTES, Y2_BYTES);
   static constexpr size_t PACKED_ELEMS = (size_t)M * C * 2 + 9 * (size_t)M * M;
   static_assert(R1MAX % 16 == 0 && R1MAX >= WW && R1MAX < 32767, "y1 rows");
+  static_assert(R1B % WR1 == 0, "conv1 row blocks split evenly over the wave rows");
   static_assert(HT > PPW * WW, "the hash table always keeps an empty slot, so probing ends");
   static_assert(WR1 * WC1 == NW && WR2 * WC2 == NW && WR3 * WC3 == NW, "wave grid");
   static_assert(M % (16 * WC1) == 0 && M % (16 * WC2) == 0 && C % (16 * WC3) == 0, "channel split");
   static_assert(NBT3 % NB3 == 0, "conv3 passes");
-  static_assert(C % KC == 0 && KC % 32 == 0 && M % 32 == 0, "k steps");
-  static_assert((KC & (KC - 1)) == 0 && KC >= 64 && KC <= 128, "x chunk pitch");
-  static_assert(MS % GS2 == 0 && MS % GS3 == 0, "weight groups stay inside one tap");
+  static_assert(C % (2 * KC) == 0 && KC == 64 && M % 32 == 0, "k steps");
+  static_assert(NSTG == 3, "x stream: three LDS stages, two chunks in flight");
+  static_assert((9 * MS) % RD2 == 0 && RD2 % MS == 0 && MS % RD3 == 0, "weight rings");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -108,6 +112,296 @@ __host__ __device__ inline int arow_channel(int base, int nb, int j, int i) {
 }
 
 __device__ inline unsigned hash_pix(int pix) { return ((unsigned)pix * 2654435761u) >> 12; }
+
+// Wave-uniform value -> scalar register, so that the compiler branches on it with scalar
+// branches instead of exec masks.
+__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Calls f(integral_constant<n>) for the run-time n in [LO, HI]: the row-block count of a
+// phase becomes a compile-time constant, so each phase's inner loop is straight-line code.
+template <int LO, int HI, class F>
+__device__ __forceinline__ void dispatch_count(int n, F&& f) {
+  if constexpr (LO >= HI) {
+    f(std::integral_constant<int, HI>{});
+  } else {
+    if (n <= LO) f(std::integral_constant<int, LO>{});
+    else dispatch_count<LO + 1, HI>(n, static_cast<F&&>(f));
+  }
+}
+
+// Workgroup barrier that waits for this wave's LDS traffic and for all but the youngest VM
+// of its global-memory operations -- NOT for all of them, as __syncthreads() would: the
+// x chunks and weights already requested for later steps stay in flight across it.
+template <int VM>
+__device__ __forceinline__ void barrier_keep_vm() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt is 6 bits");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// ---- phase 1: conv1 over the NB1*16 rows of unique window pixels -------------------------
+// x reaches LDS by direct global->LDS loads (16 bytes per lane, a wave fills 8 rows x 128 B;
+// the lane picks the global chunk whose swizzled position it writes), three stages deep;
+// the weights of the next two chunks are always in flight in registers.
+template <class K, int NB1>
+__device__ __attribute__((noinline)) void conv1_phase(const __bf16* __restrict__ x, const __bf16* __restrict__ W1,
+                                                      const float* __restrict__ b1, const int* rowpix,
+                                                      __bf16* xs, __bf16* y1s, int tid, int wave) {
+  constexpr int C = K::C, M = K::M, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
+  constexpr int RB = cdiv(NB1, K::WR1);                   // row blocks of this wave (last may be padding)
+  constexpr int NGRP = NB1 * 2, NXL = cdiv(NGRP, K::NW);  // 8-row groups; x loads per wave per chunk
+  constexpr int NWL = KS * NBW;                           // weight loads per wave per chunk
+  const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int wr = wave / K::WC1, wc = wave % K::WC1;
+
+  floatx4 acc[RB][NBW];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // x stream: group u of this wave = rows grp*8 .. grp*8+7
+  const __bf16* xsrc[NXL];
+  int xdst[NXL];                                          // element offset inside a stage (wave-uniform)
+#pragma unroll
+  for (int u = 0; u < NXL; ++u) {
+    const int grp = wave + u * K::NW;
+    if (grp < NGRP) {
+      const int row = grp * 8 + (lane >> 3), pc = lane & 7;
+      xsrc[u] = x + (size_t)rowpix[row] * C + ((pc ^ (row & 7)) << 3);
+      xdst[u] = grp * 8 * K::LDX;
+    } else {                                              // padding load: keeps the per-chunk count uniform
+      xsrc[u] = x + (size_t)rowpix[0] * C + ((lane & 7) << 3);
+      xdst[u] = K::NSTG * K::STAGE_ELEMS;
+    }
+  }
+  auto issue_x = [&](int ch) {
+    const int stage = ch % K::NSTG;
+#pragma unroll
+    for (int u = 0; u < NXL; ++u) {
+      const int off = xdst[u] == K::NSTG * K::STAGE_ELEMS ? xdst[u] : stage * K::STAGE_ELEMS + xdst[u];
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[u] + ch * K::KC), (lptr_t)(xs + off), 16, 0, 0);
+    }
+  };
+  // weights: ring of two chunks, refilled in place
+  const __bf16* wbase = W1 + (wc * NBW) * 512 + lane * 8;
+  bf16x8 w[2 * KS][NBW];
+  auto wload = [&](int slot, int kstep) {
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+      w[slot][j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)kstep * (M * 32) + j * 512);
+  };
+  int boff[RB][KS];                                       // LDS offsets of this lane's B fragments
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int row = (wr + K::WR1 * i) * 16 + l16;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) boff[i][s] = swz(row, K::LDX, s * 4 + lg, row, K::XMASK);
+  }
+
+  issue_x(0);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_x(1);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < 2 * KS; ++t) wload(t, t);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Per chunk a wave issues exactly NXL x loads, then NWL weight loads.  When it reaches the
+  // barrier of chunk ch, younger than x(ch) are at least x(ch+1) and the two latest rounds of
+  // weights; allowing NXL + NWL operations to stay in flight therefore still proves x(ch) landed.
+#pragma nounroll
+  for (int ch2 = 0; ch2 < NCH; ch2 += 2) {
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const int ch = ch2 + cc;
+      if (ch + 1 < NCH) barrier_keep_vm<NXL + NWL>(); else barrier_keep_vm<0>();
+      if (ch + 2 < NCH) issue_x(ch + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      const __bf16* xb = xs + (ch % K::NSTG) * K::STAGE_ELEMS;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+          const bf16x8 b = *reinterpret_cast<const bf16x8*>(xb + boff[i][s]);
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[cc * KS + s][j], b, acc[i][j]);
+        }
+        if (ch + 2 < NCH) wload(cc * KS + s, (ch + 2) * KS + s);
+        __builtin_amdgcn_sched_barrier(0);                 // keep the LDS reads of later steps from piling up in registers
+      }
+    }
+  }
+  // epilogue: + b1, ReLU, round to bf16
+  const int chb = wc * NBW * 16 + lg * 4 * NBW;
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int row = (wr + K::WR1 * i) * 16 + l16;
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) {
+      bf16x4 o;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b1[chb + j * 4 + v], 0.f);
+      const int c = chb + j * 4;
+      *reinterpret_cast<bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row) + (c & 7)) = o;
+    }
+  }
+}
+
+// ---- phase 2: conv3x3 as an implicit GEMM over the 9 taps, y1 rows from LDS ---------------
+template <class K, int NB2>
+__device__ __attribute__((noinline)) void conv2_phase(const __bf16* __restrict__ W2, const float* __restrict__ b2,
+                                                      const short* winrow, const __bf16* y1s, __bf16* y2s,
+                                                      int nq, int tid, int wave) {
+  constexpr int M = K::M, S = K::S, T = K::T, WW = K::WW;
+  constexpr int NBW = K::NBW2, MS = K::MS, RD = K::RD2, NSTEP = 9 * MS;
+  constexpr int RB = cdiv(NB2, K::WR2);
+  const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int wr = wave / K::WC2, wc = wave % K::WC2;
+  floatx4 acc[RB][NBW];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  int wpos[RB];                                            // window position of tap (0,0)
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int q = (wr + K::WR2 * i) * 16 + l16;
+    wpos[i] = -1;
+    if (q < nq) {
+      const int slot = q / (S * S), r = q - slot * (S * S);
+      wpos[i] = slot * WW + (r / S) * T + r % S;
+    }
+  }
+  const __bf16* wbase = W2 + (wc * NBW) * 512 + lane * 8;
+  bf16x8 w[RD][NBW];                                       // weights of the next RD k-steps, refilled in place
+  auto wload = [&](int slot, int kstep) {
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+      w[slot][j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)kstep * (M * 32) + j * 512);
+  };
+#pragma unroll
+  for (int t = 0; t < RD; ++t) wload(t, t);
+  auto lookup = [&](int (&br)[RB], int tap) {
+    const int toff = (tap / 3) * T + tap % 3;
+#pragma unroll
+    for (int i = 0; i < RB; ++i) br[i] = wpos[i] >= 0 ? winrow[wpos[i] + toff] : K::ZROW;
+  };
+  int brow[RB];
+  lookup(brow, 0);
+#pragma nounroll
+  for (int t0 = 0; t0 < NSTEP; t0 += RD) {
+#pragma unroll
+    for (int tt = 0; tt < RD; ++tt) {
+      const int t = t0 + tt;
+      const int ms = tt % MS;                              // k-step inside the tap (RD is a multiple of MS)
+      if (ms == 0 && t > 0) lookup(brow, t / MS);
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(y1s + swz(brow[i], K::LDY, ms * 4 + lg, brow[i]));
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[tt][j], b, acc[i][j]);
+      }
+      if (t + RD < NSTEP) wload(tt, t + RD);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const int chb = wc * NBW * 16 + lg * 4 * NBW;
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int q = (wr + K::WR2 * i) * 16 + l16;
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) {
+      bf16x4 o;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b2[chb + j * 4 + v], 0.f);
+      const int c = chb + j * 4;
+      *reinterpret_cast<bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q) + (c & 7)) = o;
+    }
+  }
+}
+
+// ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
+template <class K, int NB2>
+__device__ __attribute__((noinline)) void conv3_phase(const __bf16* __restrict__ x, const __bf16* __restrict__ W3,
+                                                      const float* __restrict__ b3, const int* pixq,
+                                                      const __bf16* y2s, __bf16* __restrict__ out,
+                                                      int post_relu, int tid, int wave) {
+  constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
+  constexpr int NPASS = K::NBT3 / NB, NSTEP = NPASS * MS;
+  constexpr int RB = cdiv(NB2, K::WR3);
+  const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int wr = wave / K::WC3, wc = wave % K::WC3;
+  int pq[RB], bq[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    bq[i] = (wr + K::WR3 * i) * 16 + l16;
+    pq[i] = pixq[bq[i]];
+  }
+  // this wave's weight stream is contiguous over (pass, k-step, tile)
+  const __bf16* wbase = W3 + (size_t)(wc * NPASS) * MS * NB * 512 + lane * 8;
+  bf16x8 w[RD][NB];
+  auto wload = [&](int slot, int t) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      w[slot][j] = *reinterpret_cast<const bf16x8*>(wbase + (size_t)(t * NB + j) * 512);
+  };
+#pragma unroll
+  for (int t = 0; t < RD; ++t) wload(t, t);
+#pragma nounroll
+  for (int pass = 0; pass < NPASS; ++pass) {
+    const int chb = (wc * K::NBT3 + pass * NB) * 16 + lg * 4 * NB;  // this lane's first channel
+    // residual and bias are requested before the GEMM so that their latency hides behind it
+    bf16x4 xres[RB][NB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        xres[i][j] = pq[i] >= 0 ? *reinterpret_cast<const bf16x4*>(x + (size_t)pq[i] * C + chb + j * 4)
+                                : bf16x4{(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+    float4 bias[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) bias[j] = *reinterpret_cast<const float4*>(b3 + chb + j * 4);
+    floatx4 acc[RB][NB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < MS; ++s) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(y2s + swz(bq[i], K::LDY, s * 4 + lg, bq[i]));
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(w[s % RD][j], b, acc[i][j]);
+      }
+      // refill with the step RD ahead (the stream runs on into the next pass; past its end the
+      // last step is re-read, unused)
+      wload(s % RD, min(pass * MS + s + RD, NSTEP - 1));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      if (pq[i] >= 0) {
+        const size_t off = (size_t)pq[i] * C + chb;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const float bj[4] = {bias[j].x, bias[j].y, bias[j].z, bias[j].w};
+          bf16x4 o;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            float r = (float)xres[i][j][v] + (acc[i][j][v] + bj[v]);
+            if (post_relu) r = fmaxf(r, 0.f);
+            o[v] = (__bf16)r;
+          }
+          *reinterpret_cast<bf16x4*>(out + off + j * 4) = o;
+        }
+      }
+    }
+  }
+}
 
 template <class K>
 __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
@@ -127,15 +421,15 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
   __bf16* xs = reinterpret_cast<__bf16*>(smem + K::OFF_XS);
   __bf16* y2s = xs;                                        // xs is dead once conv1 is done
 
-  constexpr int C = K::C, M = K::M, S = K::S, T = K::T, WW = K::WW;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l16 = lane & 15, lg = lane >> 4;
+  constexpr int S = K::S, T = K::T, WW = K::WW;
+  const int tid = threadIdx.x;
+  const int wave = uni(tid >> 6);
 
   // ---- which entries of the index list are this workgroup's ------------------------------
   // The list is cut into `nt` near-equal runs, nt = the number of PPW-sized tiles rounded up
   // to a multiple of `tile_slots` (workgroups the chip holds at once), so that every round
   // of workgroups is full whatever the count turns out to be.
-  const int nact = idx ? min(*count, g.P) : g.P;
+  const int nact = uni(idx ? min(*count, g.P) : g.P);
   if (nact <= 0) return;
   int nt = (nact + K::PPW - 1) / K::PPW;
   nt = (nt + tile_slots - 1) / tile_slots * tile_slots;
@@ -185,7 +479,7 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
         }
       }
       __syncthreads();
-      U = misc[0];
+      U = uni(misc[0]);
       if (U <= K::R1MAX) break;
       // too many distinct pixels for the y1 buffer: retry with fewer patches (WW <= R1MAX, so
       // one patch always fits)
@@ -210,7 +504,10 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
       }
       winrow[t] = (short)row;
     }
-    for (int r = U + tid; r < nblk1 * 16; r += K::NT) rowpix[r] = -1;
+    __syncthreads();                                       // rowpix[0] is final
+    // rows up to the block count conv1 really runs (rounded up to its wave rows) must name
+    // a valid pixel: their x is loaded and convolved, the result is never used
+    for (int r = U + tid; r < (nblk1 + K::WR1 - 1) / K::WR1 * K::WR1 * 16; r += K::NT) rowpix[r] = rowpix[0];
     for (int q = tid; q < K::R2P; q += K::NT) {
       int pix = -1;
       if (q < nq) {
@@ -225,263 +522,22 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
     __syncthreads();
     PHASE_MARK(1);
 
-    // ---------------------------------------------------------------- phase 1: conv1
-    {
-      constexpr int RBW = K::RBW1, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
-      constexpr int SEGS = K::KC / 8, NP = cdiv(K::R1MAX * SEGS, K::NT);
-      const int npiece = nblk1 * 16 * SEGS;
-      const int wr = wave / K::WC1, wc = wave % K::WC1;
-      floatx4 acc[RBW][NBW];
-#pragma unroll
-      for (int i = 0; i < RBW; ++i)
-#pragma unroll
-        for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-      const __bf16* wrow[NBW];
-#pragma unroll
-      for (int j = 0; j < NBW; ++j) wrow[j] = W1 + (wc * NBW + j) * 512 + lane * 8;
-      const __bf16* xsrc[NP];
-      int xdst[NP];
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const int piece = tid + p * K::NT;
-        xsrc[p] = nullptr;
-        xdst[p] = -1;
-        if (piece < npiece) {
-          const int row = piece / SEGS, seg = piece - row * SEGS;
-          const int pix = rowpix[row];
-          if (pix >= 0) xsrc[p] = x + (size_t)pix * C + seg * 8;
-          xdst[p] = swz(row, K::LDX, seg, row, K::XMASK);
-        }
-      }
-      uint4 xr[NP];
-      bf16x8 wa[KS][NBW], wb[KS][NBW];
-      auto gload = [&](int ch) {
-#pragma unroll
-        for (int p = 0; p < NP; ++p)
-          xr[p] = xsrc[p] ? *reinterpret_cast<const uint4*>(xsrc[p] + ch * K::KC) : uint4{0, 0, 0, 0};
-      };
-      auto sstore = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < NP; ++p)
-          if (xdst[p] >= 0) *reinterpret_cast<uint4*>(xs + buf * (K::R1MAX * K::LDX) + xdst[p]) = xr[p];
-      };
-      auto wload = [&](bf16x8(&w)[KS][NBW], int ch) {
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j)
-            w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (ch * KS + s) * (M * 32));
-      };
-      gload(0);
-      wload(wa, 0);
-      sstore(0);
-      __syncthreads();
-      for (int ch = 0; ch < NCH; ++ch) {
-        const bool more = ch + 1 < NCH;
-        if (more) {
-          gload(ch + 1);
-          wload(wb, ch + 1);
-        }
-        const __bf16* xb = xs + (ch & 1) * (K::R1MAX * K::LDX);
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-          for (int i = 0; i < RBW; ++i) {
-            const int rb = wr + K::WR1 * i;
-            if (rb < nblk1) {
-              const int row = rb * 16 + l16;
-              const bf16x8 b = *reinterpret_cast<const bf16x8*>(xb + swz(row, K::LDX, s * 4 + lg, row, K::XMASK));
-#pragma unroll
-              for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
-            }
-          }
-        if (more) {
-          sstore((ch + 1) & 1);
-#pragma unroll
-          for (int s = 0; s < KS; ++s)
-#pragma unroll
-            for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
-        }
-        __syncthreads();
-      }
-      // epilogue: + b1, ReLU, round to bf16
-      const int chb = wc * NBW * 16 + lg * 4 * NBW;
-#pragma unroll
-      for (int i = 0; i < RBW; ++i) {
-        const int rb = wr + K::WR1 * i;
-        if (rb < nblk1) {
-          const int row = rb * 16 + l16;
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) {
-            bf16x4 o;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b1[chb + j * 4 + v], 0.f);
-            const int c = chb + j * 4;
-            *reinterpret_cast<bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row) + (c & 7)) = o;
-          }
-        }
-      }
-    }
+    // Row blocks are dealt to the wave rows round-robin (wave row wr takes blocks wr, wr+WR,
+    // ...); the count is rounded up to a multiple of WR, the extra blocks compute unused rows.
+    dispatch_count<1, K::R1B / K::WR1>((nblk1 + K::WR1 - 1) / K::WR1, [&](auto nb) {
+      conv1_phase<K, decltype(nb)::value * K::WR1>(x, W1, b1, rowpix, xs, y1s, tid, wave);
+    });
     __syncthreads();
     PHASE_MARK(2);
-
-    // ---------------------------------------------------------------- phase 2: conv2 (3x3)
-    {
-      constexpr int RBW = K::RBW2, NBW = K::NBW2, GS = K::GS2, MS = K::MS;
-      constexpr int GPT = MS / GS, NG = 9 * GPT;           // groups per tap, groups in all
-      const int wr = wave / K::WC2, wc = wave % K::WC2;
-      floatx4 acc[RBW][NBW];
-#pragma unroll
-      for (int i = 0; i < RBW; ++i)
-#pragma unroll
-        for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-      int wpos[RBW];                                       // window position of tap (0,0)
-#pragma unroll
-      for (int i = 0; i < RBW; ++i) {
-        const int q = (wr + K::WR2 * i) * 16 + l16;
-        wpos[i] = -1;
-        if (q < nq) {
-          const int slot = q / (S * S), r = q - slot * (S * S);
-          wpos[i] = slot * WW + (r / S) * T + r % S;
-        }
-      }
-      const __bf16* wrow[NBW];
-#pragma unroll
-      for (int j = 0; j < NBW; ++j) wrow[j] = W2 + (wc * NBW + j) * 512 + lane * 8;
-      bf16x8 wa[GS][NBW], wb[GS][NBW];
-      auto wload = [&](bf16x8(&w)[GS][NBW], int grp) {
-#pragma unroll
-        for (int s = 0; s < GS; ++s)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j)
-            w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * (M * 32));
-      };
-      wload(wa, 0);
-      int brow[RBW];
-#pragma unroll
-      for (int i = 0; i < RBW; ++i) brow[i] = K::ZROW;
-      for (int grp = 0; grp < NG; ++grp) {
-        if (grp + 1 < NG) wload(wb, grp + 1);
-        const int tap = grp / GPT, m0 = (grp - tap * GPT) * GS * 32;
-        if (grp == tap * GPT) {                            // new tap: look the rows up
-          const int toff = (tap / 3) * T + tap % 3;
-#pragma unroll
-          for (int i = 0; i < RBW; ++i) brow[i] = wpos[i] >= 0 ? winrow[wpos[i] + toff] : K::ZROW;
-        }
-#pragma unroll
-        for (int s = 0; s < GS; ++s)
-#pragma unroll
-          for (int i = 0; i < RBW; ++i) {
-            if (wr + K::WR2 * i < nblk2) {
-              const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                  y1s + swz(brow[i], K::LDY, (m0 >> 3) + s * 4 + lg, brow[i]));
-#pragma unroll
-              for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
-            }
-          }
-        if (grp + 1 < NG) {
-#pragma unroll
-          for (int s = 0; s < GS; ++s)
-#pragma unroll
-            for (int j = 0; j < NBW; ++j) wa[s][j] = wb[s][j];
-        }
-      }
-      const int chb = wc * NBW * 16 + lg * 4 * NBW;
-#pragma unroll
-      for (int i = 0; i < RBW; ++i) {
-        const int rb = wr + K::WR2 * i;
-        if (rb < nblk2) {
-          const int q = rb * 16 + l16;
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) {
-            bf16x4 o;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][j][v] + b2[chb + j * 4 + v], 0.f);
-            const int c = chb + j * 4;
-            *reinterpret_cast<bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q) + (c & 7)) = o;
-          }
-        }
-      }
-    }
+    constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
+    dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
+      conv2_phase<K, decltype(nb)::value * WR23>(W2, b2, winrow, y1s, y2s, nq, tid, wave);
+    });
     __syncthreads();
     PHASE_MARK(3);
-
-    // ---------------------------------------------------------------- phase 3: conv3 + scatter-add
-    {
-      constexpr int RBW = K::RBW3, NB = K::NB3, GS = K::GS3, MS = K::MS, NG = MS / GS;
-      constexpr int NPASS = K::NBT3 / NB;
-      const int wr = wave / K::WC3, wc = wave % K::WC3;
-      int pq[RBW];
-#pragma unroll
-      for (int i = 0; i < RBW; ++i) {
-        const int rb = wr + K::WR3 * i;
-        pq[i] = rb < nblk2 ? pixq[rb * 16 + l16] : -1;
-      }
-      for (int pass = 0; pass < NPASS; ++pass) {
-        const int cb0 = (wc * K::NBT3 + pass * NB) * 16;   // first channel of this pass
-        floatx4 acc[RBW][NB];
-#pragma unroll
-        for (int i = 0; i < RBW; ++i)
-#pragma unroll
-          for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-        const __bf16* wrow[NB];
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-          wrow[j] = W3 + (((wc * NPASS + pass) * MS) * NB + j) * 512 + lane * 8;
-        bf16x8 wa[GS][NB], wb[GS][NB];
-        auto wload = [&](bf16x8(&w)[GS][NB], int grp) {
-#pragma unroll
-          for (int s = 0; s < GS; ++s)
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-              w[s][j] = *reinterpret_cast<const bf16x8*>(wrow[j] + (grp * GS + s) * (NB * 512));
-        };
-        wload(wa, 0);
-#pragma unroll
-        for (int grp = 0; grp < NG; ++grp) {
-          if (grp + 1 < NG) wload(wb, grp + 1);
-#pragma unroll
-          for (int s = 0; s < GS; ++s)
-#pragma unroll
-            for (int i = 0; i < RBW; ++i) {
-              const int rb = wr + K::WR3 * i;
-              if (rb < nblk2) {
-                const int q = rb * 16 + l16;
-                const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                    y2s + swz(q, K::LDY, (grp * GS + s) * 4 + lg, q));
-#pragma unroll
-                for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(wa[s][j], b, acc[i][j]);
-              }
-            }
-          if (grp + 1 < NG) {
-#pragma unroll
-            for (int s = 0; s < GS; ++s)
-#pragma unroll
-              for (int j = 0; j < NB; ++j) wa[s][j] = wb[s][j];
-          }
-        }
-        // epilogue: residual add in fp32, one rounding, store at the patch's own pixels
-        const int chb = cb0 + lg * 4 * NB;
-#pragma unroll
-        for (int i = 0; i < RBW; ++i) {
-          if (pq[i] >= 0) {
-            const size_t off = (size_t)pq[i] * C + chb;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-              const bf16x4 xv = *reinterpret_cast<const bf16x4*>(x + off + j * 4);
-              bf16x4 o;
-#pragma unroll
-              for (int v = 0; v < 4; ++v) {
-                float r = (float)xv[v] + (acc[i][j][v] + b3[chb + j * 4 + v]);
-                if (post_relu) r = fmaxf(r, 0.f);
-                o[v] = (__bf16)r;
-              }
-              *reinterpret_cast<bf16x4*>(out + off + j * 4) = o;
-            }
-          }
-        }
-      }
-    }
+    dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
+      conv3_phase<K, decltype(nb)::value * WR23>(x, W3, b3, pixq, y2s, out, post_relu, tid, wave);
+    });
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch
   }
@@ -524,14 +580,14 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const __bf16* __restr
 }
 
 // ---- instantiations --------------------------------------------------------------
-//             C     M   S PPW R1MAX NW KC  conv1  conv2+GS  conv3 NB GS
-using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // ResNet-101 stage 3, S=2
-using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // stage 3, S=7 (also the dense tile)
-using K_s2 = Cfg<512, 128, 4, 8, 256, 8, 64, 2, 4, 1, 8, 4, 1, 8, 4, 2>;      // stage 2, S=4
-using K_s2s7 = Cfg<512, 128, 7, 2, 176, 8, 64, 2, 4, 1, 8, 4, 1, 8, 4, 2>;    // stage 2, S=7 (dense tile)
-using K_s1 = Cfg<256, 64, 8, 2, 208, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;       // stage 1, S=8
-using K_s1s4 = Cfg<256, 64, 4, 8, 256, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;     // stage 1, S=4 (Table 1 block)
-using K_s1s7 = Cfg<256, 64, 7, 2, 176, 8, 64, 2, 4, 2, 4, 2, 1, 8, 2, 2>;     // stage 1, S=7 (dense tile)
+//             C     M   S PPW R1MAX NW KC NSTG conv1  conv2 RD2  conv3 NB3 RD3
+using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // ResNet-101 stage 3, S=2
+using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // stage 3, S=7 (also the dense tile)
+using K_s2 = Cfg<512, 128, 4, 8, 224, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;     // stage 2, S=4
+using K_s2s7 = Cfg<512, 128, 7, 2, 192, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;   // stage 2, S=7 (dense tile)
+using K_s1 = Cfg<256, 64, 8, 2, 224, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;       // stage 1, S=8
+using K_s1s4 = Cfg<256, 64, 4, 6, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=4 (Table 1 block)
+using K_s1s7 = Cfg<256, 64, 7, 2, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=7 (dense tile)
 
 #define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
 
