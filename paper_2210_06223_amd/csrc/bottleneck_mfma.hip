@@ -365,7 +365,9 @@ __device__ __attribute__((noinline)) void conv2_phase(g_bf16_p W2, g_f32_p b2, l
   bf16x8 bcur[RB], bnxt[RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(y1s + swz(brow[i], K::LDY, lg, brow[i]));
-#pragma nounroll
+  // fully unrolled (as in conv1): across a back edge the compiler's waits for the weight ring
+  // degrade towards vmcnt(0) and the ring stops hiding any latency
+#pragma unroll
   for (int t0 = 0; t0 < NSTEP; t0 += RD) {
 #pragma unroll
     for (int tt = 0; tt < RD; ++tt) {
