@@ -30,11 +30,21 @@
 namespace lasnet {
 namespace {
 
+// Timing experiments on conv1 (debug builds only; results are wrong when set): bit 0 no LDS
+// reads after the first chunk, 1 no barriers between chunks, 2 no x loads after the first two
+// chunks, 3 no weight loads after the first two chunks, 4 no MFMAs after the first chunk.
+#ifndef LASNET_X1
+#define LASNET_X1 0
+#endif
 #ifdef LASNET_PHASE_CLOCKS
 __device__ long long g_phase_clk[6 * 2048];
 #define PHASE_MARK(i)                                                            \
   do {                                                                           \
-    if (threadIdx.x == 0 && blockIdx.x < 2048) g_phase_clk[blockIdx.x * 6 + (i)] = wall_clock64(); \
+    if (threadIdx.x == 0 && blockIdx.x < 2048) {                                 \
+      g_phase_clk[blockIdx.x * 6 + (i)] = wall_clock64();                        \
+      if ((i) == 0) g_phase_clk[blockIdx.x * 6 + 5] = clock64();                 \
+      if ((i) == 4) g_phase_clk[blockIdx.x * 6 + 5] = clock64() - g_phase_clk[blockIdx.x * 6 + 5]; \
+    }                                                                            \
   } while (0)
 #else
 #define PHASE_MARK(i) do { } while (0)
@@ -147,6 +157,9 @@ __device__ __forceinline__ bf16x8 join8(bf16x4 a, bf16x4 b) {
 // to itself); their pointer parameters carry explicit address spaces, otherwise every LDS
 // access would go through a generic-pointer conversion and every weight load would be a
 // FLAT load, which also counts on lgkmcnt and so would be waited for with each LDS read.
+#ifndef LASNET_PHASE_INLINE
+#define LASNET_PHASE_INLINE __attribute__((always_inline))
+#endif
 #define AS_GLOBAL __attribute__((address_space(1)))
 #define AS_LDS __attribute__((address_space(3)))
 typedef const AS_GLOBAL void* gptr_t;
@@ -158,18 +171,44 @@ typedef const AS_LDS __bf16* l_bf16_cp;
 typedef const AS_LDS int* l_i32_cp;
 typedef const AS_LDS short* l_i16_cp;
 
+// A wave-uniform global pointer that arrived in vector registers (function arguments do)
+// -> scalar registers, so that loads through it can take the "scalar base + 32-bit lane
+// offset" form: stepping through the weight stream then costs scalar adds only, and no
+// vector register pair per load address.
+__device__ __forceinline__ g_bf16_p uni_ptr(g_bf16_p p) {
+  const unsigned long long v = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (g_bf16_p)(((unsigned long long)hi << 32) | lo);
+}
+
+// Weights are read with buffer loads: the address is a buffer descriptor (4 scalar registers,
+// once per tensor) + a scalar byte offset (the position in the weight stream, wave-uniform)
+// + one vector register holding lane * 16 + a 12-bit immediate.  No vector register pair
+// and no vector adds per load address, which is what kept the phases from fitting the
+// register file when they are inlined into the kernel.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(g_bf16_p p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(unsigned long long)uni_ptr(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ bf16x8 buf_load16(rsrc_t r, int lane_bytes, int uniform_bytes) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, lane_bytes, uniform_bytes, 0));
+}
+
 // ---- phase 1: conv1 over the NB1*16 rows of unique window pixels -------------------------
 // x reaches LDS by direct global->LDS loads (16 bytes per lane, a wave fills 8 rows x 128 B;
 // the lane picks the global chunk whose swizzled position it writes), three stages deep;
 // the weights of the next two chunks are always in flight in registers.
 template <class K, int NB1>
-__device__ __attribute__((noinline)) void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p b1, l_i32_cp rowpix,
+__device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p b1, l_i32_cp rowpix,
                                                       l_bf16_p xs, l_bf16_p y1s, int tid, int wave) {
   constexpr int C = K::C, M = K::M, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
   constexpr int RB = cdiv(NB1, K::WR1);                   // row blocks of this wave (last may be padding)
   constexpr int NGRP = NB1 * 2, NXL = cdiv(NGRP, K::NW);  // 8-row groups; x loads per wave per chunk
   constexpr int NWL = KS * NBW;                           // weight loads per wave per chunk
   const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int lane16 = lane * 16;
+  wave = uni(wave);
   const int wr = wave / K::WC1, wc = wave % K::WC1;
 
   floatx4 acc[RB][NBW];
@@ -186,11 +225,7 @@ __device__ __attribute__((noinline)) void conv1_phase(g_bf16_p x, g_bf16_p W1, g
     const int grp = wave + u * K::NW;
     if (grp < NGRP) {
       const int row = grp * 8 + (lane >> 3), pc = lane & 7;
-#if defined(LASNET_EXP) && (LASNET_EXP == 4 || LASNET_EXP == 6)
-      xsrc[u] = x + (size_t)rowpix[row & 7] * C + ((pc ^ (row & 7)) << 3);   // timing experiment: 8 hot rows
-#else
       xsrc[u] = x + (size_t)rowpix[row] * C + ((pc ^ (row & 7)) << 3);
-#endif
       xdst[u] = grp * 8 * K::LDX;
     } else {                                              // padding load: keeps the per-chunk count uniform
       xsrc[u] = x + (size_t)rowpix[0] * C + ((lane & 7) << 3);
@@ -213,15 +248,13 @@ __device__ __attribute__((noinline)) void conv1_phase(g_bf16_p x, g_bf16_p W1, g
     }
   };
   // weights: ring of two chunks, refilled in place
-  g_bf16_p wbase = W1 + (wc * NBW) * 512 + lane * 8;
+  const rsrc_t wrs = make_rsrc(W1, (unsigned)(M * C * 2));
+  const int wbase = (wc * NBW) * 1024;                     // bytes, wave-uniform
   bf16x8 w[2 * KS][NBW];
   auto wload = [&](int slot, int kstep) {
-#if defined(LASNET_EXP) && (LASNET_EXP == 5 || LASNET_EXP == 6)
-    kstep &= 1;                                            // timing experiment: weights from an L1-resident slab
-#endif
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-      w[slot][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(wbase + (size_t)kstep * (M * 32) + j * 512);
+      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * (M * 64));
   };
   int boff[RB][KS];                                       // LDS offsets of this lane's B fragments
 #pragma unroll
@@ -257,30 +290,34 @@ __device__ __attribute__((noinline)) void conv1_phase(g_bf16_p x, g_bf16_p W1, g
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const int ch = ch2 + cc;
+#if (LASNET_X1 & 2)
+      if (ch == 0 || ch + 1 == NCH) { if (ch + 1 < NCH) barrier_keep_vm<NXL + NWL>(); else barrier_keep_vm<0>(); }
+#else
       if (ch + 1 < NCH) barrier_keep_vm<NXL + NWL>(); else barrier_keep_vm<0>();
+#endif
       __builtin_amdgcn_sched_barrier(0);
       l_bf16_cp xb = xs + (ch % K::NSTG) * K::STAGE_ELEMS;
 #pragma unroll
-      for (int i = 0; i < RB; ++i) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][0]);
+      for (int i = 0; i < RB; ++i) if (!(LASNET_X1 & 1) || ch == 0) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][0]);
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        if (s + 1 < KS) {
+        if (s + 1 < KS && (!(LASNET_X1 & 1) || ch == 0)) {
 #pragma unroll
           for (int i = 0; i < RB; ++i) bnxt[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][s + 1]);
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i)
 #pragma unroll
-          for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[cc * KS + s][j], bcur[i], acc[i][j]);
-        if (ch + 2 < NCH) wload(cc * KS + s, (ch + 2) * KS + s);
+          for (int j = 0; j < NBW; ++j) if (!(LASNET_X1 & 16) || ch == 0) acc[i][j] = mfma16(w[cc * KS + s][j], bcur[i], acc[i][j]);
+        if (ch + 2 < NCH && !(LASNET_X1 & 8)) wload(cc * KS + s, (ch + 2) * KS + s);
         __builtin_amdgcn_sched_barrier(0);
-        if (s + 1 < KS) {
+        if (s + 1 < KS && (!(LASNET_X1 & 1) || ch == 0)) {
 #pragma unroll
           for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
         }
       }
       // stage (ch+2)%3 was read during chunk ch-1, which every wave has left (barrier above)
-      if (ch + 2 < NCH) issue_x(ch + 2);
+      if (ch + 2 < NCH && !(LASNET_X1 & 4)) issue_x(ch + 2);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -315,12 +352,14 @@ __device__ __attribute__((noinline)) void conv1_phase(g_bf16_p x, g_bf16_p W1, g
 
 // ---- phase 2: conv3x3 as an implicit GEMM over the 9 taps, y1 rows from LDS ---------------
 template <class K, int NB2>
-__device__ __attribute__((noinline)) void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_cp winrow, l_bf16_cp y1s,
+__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_cp winrow, l_bf16_cp y1s,
                                                       l_bf16_p y2s, int nq, int tid, int wave) {
   constexpr int M = K::M, S = K::S, T = K::T, WW = K::WW;
   constexpr int NBW = K::NBW2, MS = K::MS, RD = K::RD2, NSTEP = 9 * MS;
   constexpr int RB = cdiv(NB2, K::WR2);
   const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int lane16 = lane * 16;
+  wave = uni(wave);
   const int wr = wave / K::WC2, wc = wave % K::WC2;
   floatx4 acc[RB][NBW];
 #pragma unroll
@@ -337,15 +376,13 @@ __device__ __attribute__((noinline)) void conv2_phase(g_bf16_p W2, g_f32_p b2, l
       wpos[i] = slot * WW + (r / S) * T + r % S;
     }
   }
-  g_bf16_p wbase = W2 + (wc * NBW) * 512 + lane * 8;
+  const rsrc_t wrs = make_rsrc(W2, (unsigned)(9 * M * M * 2));
+  const int wbase = (wc * NBW) * 1024;                     // bytes, wave-uniform
   bf16x8 w[RD][NBW];                                       // weights of the next RD k-steps, refilled in place
   auto wload = [&](int slot, int kstep) {
-#if defined(LASNET_EXP) && (LASNET_EXP == 1 || LASNET_EXP == 3)
-    kstep &= 1;                                            // timing experiment: weights from an L1-resident slab
-#endif
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-      w[slot][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(wbase + (size_t)kstep * (M * 32) + j * 512);
+      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * (M * 64));
   };
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
@@ -353,10 +390,6 @@ __device__ __attribute__((noinline)) void conv2_phase(g_bf16_p W2, g_f32_p b2, l
     const int toff = (tap / 3) * T + tap % 3;
 #pragma unroll
     for (int i = 0; i < RB; ++i) br[i] = wpos[i] >= 0 ? winrow[wpos[i] + toff] : K::ZROW;
-#if defined(LASNET_EXP) && (LASNET_EXP == 2 || LASNET_EXP == 3)
-#pragma unroll
-    for (int i = 0; i < RB; ++i) br[i] = i * 16 + l16;     // timing experiment: consecutive rows, conflict-free
-#endif
   };
   int brow[RB];
   lookup(brow, 0);
@@ -419,13 +452,15 @@ __device__ __attribute__((noinline)) void conv2_phase(g_bf16_p W2, g_f32_p b2, l
 
 // ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
 template <class K, int NB2>
-__device__ __attribute__((noinline)) void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p b3, l_i32_cp pixq,
+__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p b3, l_i32_cp pixq,
                                                       l_bf16_cp y2s, AS_GLOBAL __bf16* out,
                                                       int post_relu, int tid, int wave) {
   constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
   constexpr int NPASS = K::NBT3 / NB, NSTEP = NPASS * MS;
   constexpr int RB = cdiv(NB2, K::WR3);
   const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  const int lane16 = lane * 16;
+  wave = uni(wave);
   const int wr = wave / K::WC3, wc = wave % K::WC3;
   int pq[RB], bq[RB];
 #pragma unroll
@@ -434,15 +469,13 @@ __device__ __attribute__((noinline)) void conv3_phase(g_bf16_p x, g_bf16_p W3, g
     pq[i] = pixq[bq[i]];
   }
   // this wave's weight stream is contiguous over (pass, k-step, tile)
-  g_bf16_p wbase = W3 + (size_t)(wc * NPASS) * MS * NB * 512 + lane * 8;
+  const rsrc_t wrs = make_rsrc(W3, (unsigned)(C * K::M * 2));
+  const int wbase = (wc * NPASS) * MS * NB * 1024;         // bytes, wave-uniform
   bf16x8 w[RD][NB];
   auto wload = [&](int slot, int t) {
-#if defined(LASNET_EXP) && (LASNET_EXP == 8 || LASNET_EXP == 9)
-    t &= 1;                                                // timing experiment: hot weights
-#endif
 #pragma unroll
     for (int j = 0; j < NB; ++j)
-      w[slot][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(wbase + (size_t)(t * NB + j) * 512);
+      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * (NB * 1024));
   };
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
@@ -455,12 +488,8 @@ __device__ __attribute__((noinline)) void conv3_phase(g_bf16_p x, g_bf16_p W3, g
     for (int i = 0; i < RB; ++i)
 #pragma unroll
       for (int j = 0; j < NB / 2; ++j)
-#if defined(LASNET_EXP) && (LASNET_EXP == 7 || LASNET_EXP == 9)
-        xres[i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + chb + j * 8);   // timing experiment: hot residual
-#else
         xres[i][j] = pq[i] >= 0 ? *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)pq[i] * C + chb + j * 8)
                                 : bf16x8{};
-#endif
     floatx4 bias[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) bias[j] = *reinterpret_cast<const AS_GLOBAL floatx4*>(b3 + chb + j * 4);
@@ -508,9 +537,6 @@ __device__ __attribute__((noinline)) void conv3_phase(g_bf16_p x, g_bf16_p W3, g
               o[h * 4 + v] = (__bf16)r;
             }
           }
-#if defined(LASNET_EXP) && LASNET_EXP == 10
-          if (o[0] == (__bf16)12345.f)                     // timing experiment: (almost) no output stores
-#endif
           *reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + j * 4) = o;
         }
       }
@@ -550,8 +576,13 @@ __global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
   nt = (nt + tile_slots - 1) / tile_slots * tile_slots;
   nt = min(min(nt, (int)gridDim.x), nact);
   if ((int)blockIdx.x >= nt) return;                       // uniform over the workgroup
-  const int tb = (int)(((long long)blockIdx.x * nact) / nt);
-  const int te = (int)(((long long)(blockIdx.x + 1) * nact) / nt);
+  // Workgroup b runs on XCD b % 8 (round-robin dispatch), and each XCD has its own L2.  Runs
+  // that are neighbours in the list share window pixels, so XCD k takes a contiguous eighth
+  // of the runs: the shared rows are then fetched into one L2 once, not into two.
+  const int xcd = (int)blockIdx.x & 7, jx = (int)blockIdx.x >> 3;
+  const int tile = xcd * (nt >> 3) + min(xcd, nt & 7) + jx;   // jx < runs of this XCD because b < nt
+  const int tb = (int)(((long long)tile * nact) / nt);
+  const int te = (int)(((long long)(tile + 1) * nact) / nt);
   PHASE_MARK(0);
 
   // the all-zero y1 row
