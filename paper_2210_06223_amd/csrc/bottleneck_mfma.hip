@@ -110,15 +110,60 @@ struct Cfg {
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
+// Pointers into global memory and LDS carry explicit address spaces: through generic pointers
+// every LDS access would need a conversion and every weight load would be a FLAT load, which
+// also counts on lgkmcnt and so would be waited for with each LDS read.  The phase functions
+// are inlined into the kernel by default (a real call saves and restores half of the vector
+// registers through scratch memory on every call).
+#ifndef LASNET_PHASE_INLINE
+#define LASNET_PHASE_INLINE __attribute__((always_inline))
+#endif
+#define AS_GLOBAL __attribute__((address_space(1)))
+#define AS_LDS __attribute__((address_space(3)))
+typedef const AS_GLOBAL void* gptr_t;
+typedef AS_LDS void* lptr_t;
+typedef const AS_GLOBAL __bf16* g_bf16_p;      // read-only global bf16
+typedef const AS_GLOBAL float* g_f32_p;
+typedef AS_LDS __bf16* l_bf16_p;
+typedef const AS_LDS __bf16* l_bf16_cp;
+typedef const AS_LDS int* l_i32_cp;
+typedef const AS_LDS short* l_i16_cp;
+
 // Element offset of 16-byte chunk `chunk` in an LDS row of pitch `ld` elements whose chunks
 // are XOR-swizzled with `key` (low 4 bits of the chunk index at most).
 __device__ inline int swz(int row, int ld, int chunk, int key, int mask = 15) {
   return row * ld + ((chunk ^ (key & mask)) << 3);
 }
 
-// Channel held by A-operand row i (0..15) of tile j when NB tiles are interleaved.
+// The same address for the B-fragment reads of the k-loops, split so that the part that changes
+// with the k-step is a compile-time constant: chunk = 4*s + lg never carries, so
+// (4*s + lg) ^ key = (4*s) ^ (lg ^ key), and in bytes the fragment of k-step s sits at
+//   row_bytes + ((64*s) ^ key_bytes),   key_bytes = (lg ^ (key & mask)) << 4.
+// One xor-add per read and two registers per row, instead of one register per (row, k-step).
+struct FragRow { int row_bytes, key_bytes; };
+__device__ __forceinline__ FragRow frag_row(int row, int ld, int lg, int key, int mask = 15) {
+  return FragRow{row * ld * 2, (lg ^ (key & mask)) << 4};
+}
+__device__ __forceinline__ bf16x8 frag_read(const AS_LDS __bf16* base, FragRow r, int s) {
+  return *reinterpret_cast<const AS_LDS bf16x8*>(reinterpret_cast<const AS_LDS char*>(base) + r.row_bytes +
+                                                 ((64 * s) ^ r.key_bytes));
+}
+
+// Which output channel a lane holds.  In the 16x16 result of an MFMA, lane group lg (= lane / 16)
+// holds rows 4*lg .. 4*lg+3 in its 4 accumulator elements v.  A pass computes nb tiles (j) of
+// 16 channels each; which channel is row i of tile j is free (the weights are repacked to
+// match), and it is chosen so that what a lane holds of tiles 2t and 2t+1 are 8 consecutive
+// channels, and the four lane groups together 32 consecutive ones:
+//   channel = base + 32*(j/2) + 8*lg + 4*(j%2) + v            (nb even)
+// One 16-byte store per lane then writes 64 contiguous bytes per pixel (whole HBM bursts),
+// and the same 16 bytes are one swizzle chunk of an LDS row.  nb odd: base + 4*nb*lg + 4*j + v.
+__host__ __device__ inline int lane_channel(int base, int nb, int j, int lg, int v) {
+  return (nb & 1) ? base + lg * (4 * nb) + j * 4 + v
+                  : base + (j >> 1) * 32 + lg * 8 + (j & 1) * 4 + v;
+}
+// Channel whose weights sit in A-operand row i (0..15) of tile j.
 __host__ __device__ inline int arow_channel(int base, int nb, int j, int i) {
-  return base + (i >> 2) * (4 * nb) + j * 4 + (i & 3);
+  return lane_channel(base, nb, j, i >> 2, i & 3);
 }
 
 __device__ inline unsigned hash_pix(int pix) { return ((unsigned)pix * 2654435761u) >> 12; }
@@ -153,23 +198,6 @@ __device__ __forceinline__ bf16x8 join8(bf16x4 a, bf16x4 b) {
   return bf16x8{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
 }
 
-// The phase functions below are real calls (noinline keeps each phase's register allocation
-// to itself); their pointer parameters carry explicit address spaces, otherwise every LDS
-// access would go through a generic-pointer conversion and every weight load would be a
-// FLAT load, which also counts on lgkmcnt and so would be waited for with each LDS read.
-#ifndef LASNET_PHASE_INLINE
-#define LASNET_PHASE_INLINE __attribute__((always_inline))
-#endif
-#define AS_GLOBAL __attribute__((address_space(1)))
-#define AS_LDS __attribute__((address_space(3)))
-typedef const AS_GLOBAL void* gptr_t;
-typedef AS_LDS void* lptr_t;
-typedef const AS_GLOBAL __bf16* g_bf16_p;      // read-only global bf16
-typedef const AS_GLOBAL float* g_f32_p;
-typedef AS_LDS __bf16* l_bf16_p;
-typedef const AS_LDS __bf16* l_bf16_cp;
-typedef const AS_LDS int* l_i32_cp;
-typedef const AS_LDS short* l_i16_cp;
 
 // A wave-uniform global pointer that arrived in vector registers (function arguments do)
 // -> scalar registers, so that loads through it can take the "scalar base + 32-bit lane
@@ -322,12 +350,12 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
     }
   }
   // epilogue: + b1, ReLU, round to bf16; 8 channels (one 16-byte chunk) per LDS store where NBW allows
-  const int chb = wc * NBW * 16 + lg * 4 * NBW;
+  const int chb = wc * NBW * 16;
   float bias[NBW][4];
 #pragma unroll
   for (int j = 0; j < NBW; ++j)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) bias[j][v] = b1[chb + j * 4 + v];
+    for (int v = 0; v < 4; ++v) bias[j][v] = b1[lane_channel(chb, NBW, j, lg, v)];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int row = (wr + K::WR1 * i) * 16 + l16;
@@ -339,11 +367,11 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
-        *reinterpret_cast<AS_LDS bf16x8*>(y1s + swz(row, K::LDY, (chb + j * 4) >> 3, row)) = join8(o[j], o[j + 1]);
+        *reinterpret_cast<AS_LDS bf16x8*>(y1s + swz(row, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, row)) = join8(o[j], o[j + 1]);
     } else {
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
-        const int c = chb + j * 4;
+        const int c = lane_channel(chb, NBW, j, lg, 0);
         *reinterpret_cast<AS_LDS bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row) + (c & 7)) = o[j];
       }
     }
@@ -392,12 +420,15 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
     for (int i = 0; i < RB; ++i) br[i] = wpos[i] >= 0 ? winrow[wpos[i] + toff] : K::ZROW;
   };
   int brow[RB];
+  FragRow fr[RB];
   lookup(brow, 0);
+#pragma unroll
+  for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i]);
   // B fragments one k-step ahead of the MFMAs (bcur/bnxt); the row lookup of the next tap
   // happens while the last k-step of the current one is computed.
   bf16x8 bcur[RB], bnxt[RB];
 #pragma unroll
-  for (int i = 0; i < RB; ++i) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(y1s + swz(brow[i], K::LDY, lg, brow[i]));
+  for (int i = 0; i < RB; ++i) bcur[i] = frag_read(y1s, fr[i], 0);
   // fully unrolled (as in conv1): across a back edge the compiler's waits for the weight ring
   // degrade towards vmcnt(0) and the ring stops hiding any latency
 #pragma unroll
@@ -407,10 +438,13 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
       const int t = t0 + tt;
       const int msn = (tt + 1) % MS;                       // k-step inside the tap of step t+1 (RD is a multiple of MS)
       if (t + 1 < NSTEP) {
-        if (msn == 0) lookup(brow, (t + 1) / MS);
+        if (msn == 0) {
+          lookup(brow, (t + 1) / MS);
 #pragma unroll
-        for (int i = 0; i < RB; ++i)
-          bnxt[i] = *reinterpret_cast<const AS_LDS bf16x8*>(y1s + swz(brow[i], K::LDY, msn * 4 + lg, brow[i]));
+          for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) bnxt[i] = frag_read(y1s, fr[i], msn);
       }
 #pragma unroll
       for (int i = 0; i < RB; ++i)
@@ -422,12 +456,12 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
       for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
     }
   }
-  const int chb = wc * NBW * 16 + lg * 4 * NBW;
+  const int chb = wc * NBW * 16;
   float bias[NBW][4];
 #pragma unroll
   for (int j = 0; j < NBW; ++j)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) bias[j][v] = b2[chb + j * 4 + v];
+    for (int v = 0; v < 4; ++v) bias[j][v] = b2[lane_channel(chb, NBW, j, lg, v)];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int q = (wr + K::WR2 * i) * 16 + l16;
@@ -439,11 +473,11 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
-        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY, (chb + j * 4) >> 3, q)) = join8(o[j], o[j + 1]);
+        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, q)) = join8(o[j], o[j + 1]);
     } else {
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
-        const int c = chb + j * 4;
+        const int c = lane_channel(chb, NBW, j, lg, 0);
         *reinterpret_cast<AS_LDS bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q) + (c & 7)) = o[j];
       }
     }
@@ -462,11 +496,13 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
   const int lane16 = lane * 16;
   wave = uni(wave);
   const int wr = wave / K::WC3, wc = wave % K::WC3;
-  int pq[RB], bq[RB];
+  int pq[RB];
+  FragRow fr[RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
-    bq[i] = (wr + K::WR3 * i) * 16 + l16;
-    pq[i] = pixq[bq[i]];
+    const int bq = (wr + K::WR3 * i) * 16 + l16;
+    pq[i] = pixq[bq];
+    fr[i] = frag_row(bq, K::LDY, lg, bq);
   }
   // this wave's weight stream is contiguous over (pass, k-step, tile)
   const rsrc_t wrs = make_rsrc(W3, (unsigned)(C * K::M * 2));
@@ -479,20 +515,20 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
   };
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
-#pragma nounroll
+  // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
+#pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
-    const int chb = (wc * K::NBT3 + pass * NB) * 16 + lg * 4 * NB;  // this lane's first channel
+    const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
     // residual and bias are requested before the GEMM so that their latency hides behind it
     bf16x8 xres[RB][NB / 2];
 #pragma unroll
     for (int i = 0; i < RB; ++i)
 #pragma unroll
-      for (int j = 0; j < NB / 2; ++j)
-        xres[i][j] = pq[i] >= 0 ? *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)pq[i] * C + chb + j * 8)
-                                : bf16x8{};
+      for (int j = 0; j < NB / 2; ++j)   // rows past the last pixel read pixel 0 (never stored)
+        xres[i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq[i], 0) * C + lane_channel(chb, NB, 2 * j, lg, 0));
     floatx4 bias[NB];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bias[j] = *reinterpret_cast<const AS_GLOBAL floatx4*>(b3 + chb + j * 4);
+    for (int j = 0; j < NB; ++j) bias[j] = *reinterpret_cast<const AS_GLOBAL floatx4*>(b3 + lane_channel(chb, NB, j, lg, 0));
     floatx4 acc[RB][NB];
 #pragma unroll
     for (int i = 0; i < RB; ++i)
@@ -500,13 +536,12 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
       for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
     bf16x8 bcur[RB], bnxt[RB];
 #pragma unroll
-    for (int i = 0; i < RB; ++i) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(y2s + swz(bq[i], K::LDY, lg, bq[i]));
+    for (int i = 0; i < RB; ++i) bcur[i] = frag_read(y2s, fr[i], 0);
 #pragma unroll
     for (int s = 0; s < MS; ++s) {
       if (s + 1 < MS) {
 #pragma unroll
-        for (int i = 0; i < RB; ++i)
-          bnxt[i] = *reinterpret_cast<const AS_LDS bf16x8*>(y2s + swz(bq[i], K::LDY, (s + 1) * 4 + lg, bq[i]));
+        for (int i = 0; i < RB; ++i) bnxt[i] = frag_read(y2s, fr[i], s + 1);
       }
 #pragma unroll
       for (int i = 0; i < RB; ++i)
@@ -524,7 +559,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
       if (pq[i] >= 0) {
-        const size_t off = (size_t)pq[i] * C + chb;
+        const size_t off = (size_t)pq[i] * C;
 #pragma unroll
         for (int j = 0; j < NB; j += 2) {
           bf16x8 o;
@@ -537,7 +572,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
               o[h * 4 + v] = (__bf16)r;
             }
           }
-          *reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + j * 4) = o;
+          *reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + lane_channel(chb, NB, j, lg, 0)) = o;
         }
       }
     }

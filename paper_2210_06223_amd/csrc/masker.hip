@@ -17,8 +17,33 @@ __device__ inline double wave_sum(double v) {
 
 __device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
-// One wave per cell.  VEC = true: 16-byte loads (needs C*sizeof(T) % 16 == 0, aligned base).
-template <typename T, bool VEC>
+// acc += sum over the V elements of one 16-byte piece of x times their masker weights.
+__device__ inline void fma_piece(double& acc, const uint4& q, const float4& w0, const float4& w1,
+                                 uint16_t /*bf16 tag*/) {
+  acc = fma((double)w0.x, (double)bf16_bits_to_float(q.x & 0xffffu), acc);
+  acc = fma((double)w0.y, (double)bf16_bits_to_float(q.x >> 16), acc);
+  acc = fma((double)w0.z, (double)bf16_bits_to_float(q.y & 0xffffu), acc);
+  acc = fma((double)w0.w, (double)bf16_bits_to_float(q.y >> 16), acc);
+  acc = fma((double)w1.x, (double)bf16_bits_to_float(q.z & 0xffffu), acc);
+  acc = fma((double)w1.y, (double)bf16_bits_to_float(q.z >> 16), acc);
+  acc = fma((double)w1.z, (double)bf16_bits_to_float(q.w & 0xffffu), acc);
+  acc = fma((double)w1.w, (double)bf16_bits_to_float(q.w >> 16), acc);
+}
+__device__ inline void fma_piece(double& acc, const uint4& q, const float4& w0, const float4&,
+                                 float /*f32 tag*/) {
+  acc = fma((double)w0.x, (double)__uint_as_float(q.x), acc);
+  acc = fma((double)w0.y, (double)__uint_as_float(q.y), acc);
+  acc = fma((double)w0.z, (double)__uint_as_float(q.z), acc);
+  acc = fma((double)w0.w, (double)__uint_as_float(q.w), acc);
+}
+
+// One wave per cell.  A patch row is one contiguous segment of S*C elements; a wave reads it
+// in groups of four 1 KiB pieces (16 bytes per lane each) that are all requested before the
+// first one is used, so that enough bytes are in flight to keep HBM busy.
+// VEC: 16-byte loads (needs C*sizeof(T) % 16 == 0 and aligned bases).  HOIST: the segment is
+// exactly one group (S*C*sizeof(T) == 4 KiB, true for every ResNet stage in bf16), so a lane
+// meets the same channels in every row and keeps their masker weights in registers.
+template <typename T, bool VEC, bool HOIST>
 __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
     const T* __restrict__ x, const float* __restrict__ Wm, double bm, double thr, int S, int H,
     int W, int C, int G, int GW, int P, uint8_t* __restrict__ mask, double* __restrict__ logits) {
@@ -28,40 +53,70 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
   const int n = cell / (G * GW);
   const int rem = cell - n * (G * GW);
   const int gy = rem / GW, gx = rem - gy * GW;
-  constexpr int V = VEC ? (16 / (int)sizeof(T)) : 1;
   const int seg = S * C;                      // contiguous elements of one patch row
-  double acc = 0.0;
-  for (int i = 0; i < S; ++i) {
-    const T* row = x + ((size_t)(n * H + gy * S + i) * W + (size_t)gx * S) * C;
-    for (int e = lane * V; e < seg; e += 64 * V) {
-      const int c = e % C;
-      if constexpr (VEC && sizeof(T) == 2) {
-        const uint4 q = *reinterpret_cast<const uint4*>(row + e);
-        const float4 w0 = *reinterpret_cast<const float4*>(Wm + c);
-        const float4 w1 = *reinterpret_cast<const float4*>(Wm + c + 4);
-        acc = fma((double)w0.x, (double)bf16_bits_to_float(q.x & 0xffffu), acc);
-        acc = fma((double)w0.y, (double)bf16_bits_to_float(q.x >> 16), acc);
-        acc = fma((double)w0.z, (double)bf16_bits_to_float(q.y & 0xffffu), acc);
-        acc = fma((double)w0.w, (double)bf16_bits_to_float(q.y >> 16), acc);
-        acc = fma((double)w1.x, (double)bf16_bits_to_float(q.z & 0xffffu), acc);
-        acc = fma((double)w1.y, (double)bf16_bits_to_float(q.z >> 16), acc);
-        acc = fma((double)w1.z, (double)bf16_bits_to_float(q.w & 0xffffu), acc);
-        acc = fma((double)w1.w, (double)bf16_bits_to_float(q.w >> 16), acc);
-      } else if constexpr (VEC && sizeof(T) == 4) {
-        const float4 q = *reinterpret_cast<const float4*>(row + e);
-        const float4 w0 = *reinterpret_cast<const float4*>(Wm + c);
-        acc = fma((double)w0.x, (double)q.x, acc);
-        acc = fma((double)w0.y, (double)q.y, acc);
-        acc = fma((double)w0.z, (double)q.z, acc);
-        acc = fma((double)w0.w, (double)q.w, acc);
-      } else if constexpr (sizeof(T) == 2) {
-        acc = fma((double)Wm[c], (double)bf16_bits_to_float(row[e]), acc);
-      } else {
-        acc = fma((double)Wm[c], (double)row[e], acc);
+  const T* cell0 = x + ((size_t)(n * H + gy * S) * W + (size_t)gx * S) * C;
+  const size_t pitch = (size_t)W * C;         // elements between patch rows
+  double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+  if constexpr (VEC) {
+    constexpr int V = 16 / (int)sizeof(T);    // elements per 16-byte piece
+    constexpr int GRP = 4 * 64 * V;           // elements per group of four pieces
+    if constexpr (HOIST) {
+      float4 w[4][2];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = ((lane + 64 * u) * V) % C;
+        w[u][0] = *reinterpret_cast<const float4*>(Wm + c);
+        w[u][1] = V == 8 ? *reinterpret_cast<const float4*>(Wm + c + 4) : float4{0.f, 0.f, 0.f, 0.f};
+      }
+      for (int i = 0; i < S; ++i) {
+        const T* row = cell0 + i * pitch;
+        uint4 q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4*>(row + (lane + 64 * u) * V);
+        fma_piece(acc0, q[0], w[0][0], w[0][1], T{});
+        fma_piece(acc1, q[1], w[1][0], w[1][1], T{});
+        fma_piece(acc2, q[2], w[2][0], w[2][1], T{});
+        fma_piece(acc3, q[3], w[3][0], w[3][1], T{});
+      }
+    } else {
+      for (int i = 0; i < S; ++i) {
+        const T* row = cell0 + i * pitch;
+        int e0 = 0;
+        for (; e0 + GRP <= seg; e0 += GRP) {
+          uint4 q[4];
+          float4 w[4][2];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = e0 + (lane + 64 * u) * V, c = e % C;
+            q[u] = *reinterpret_cast<const uint4*>(row + e);
+            w[u][0] = *reinterpret_cast<const float4*>(Wm + c);
+            w[u][1] = V == 8 ? *reinterpret_cast<const float4*>(Wm + c + 4) : float4{0.f, 0.f, 0.f, 0.f};
+          }
+          fma_piece(acc0, q[0], w[0][0], w[0][1], T{});
+          fma_piece(acc1, q[1], w[1][0], w[1][1], T{});
+          fma_piece(acc2, q[2], w[2][0], w[2][1], T{});
+          fma_piece(acc3, q[3], w[3][0], w[3][1], T{});
+        }
+        for (int e = e0 + lane * V; e < seg; e += 64 * V) {      // pieces left over
+          const int c = e % C;
+          const uint4 q = *reinterpret_cast<const uint4*>(row + e);
+          const float4 w0 = *reinterpret_cast<const float4*>(Wm + c);
+          const float4 w1 = V == 8 ? *reinterpret_cast<const float4*>(Wm + c + 4) : float4{0.f, 0.f, 0.f, 0.f};
+          fma_piece(acc0, q, w0, w1, T{});
+        }
+      }
+    }
+  } else {
+    for (int i = 0; i < S; ++i) {
+      const T* row = cell0 + i * pitch;
+      for (int e = lane; e < seg; e += 64) {
+        const int c = e % C;
+        if constexpr (sizeof(T) == 2) acc0 = fma((double)Wm[c], (double)bf16_bits_to_float(row[e]), acc0);
+        else acc0 = fma((double)Wm[c], (double)row[e], acc0);
       }
     }
   }
-  acc = wave_sum(acc);
+  const double acc = wave_sum((acc0 + acc1) + (acc2 + acc3));
   if (lane == 0) {
     const double logit = bm + acc / (double)(S * S);
     if (logits) logits[cell] = logit;
@@ -69,24 +124,43 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
   }
 }
 
-// Ordered stream compaction by one workgroup: wave ballot + popcount gives each active
-// cell its rank inside its wave, a scan over the 16 wave totals its rank inside the
-// 1024-cell chunk, and a running base its rank overall.  Integer work only: the list is
-// the ascending sequence of active cell ids whatever the timing.
+// Ordered stream compaction by one workgroup.  A thread takes V consecutive cells (one 8-byte
+// load when V = 8), a shuffle scan over the per-thread counts gives each thread its rank
+// inside its wave, a scan over the 16 wave totals its rank inside the 1024*V-cell round, and
+// a running base its rank overall.  Integer work only: the list is the ascending sequence
+// of active cell ids whatever the timing.
 constexpr int kCompactThreads = 1024;
 
+template <int V>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const uint8_t* __restrict__ mask, int P, int32_t* __restrict__ idx,
     int32_t* __restrict__ count) {
   __shared__ int wave_tot[kCompactThreads / 64];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int base = 0;                                // identical in every thread
-  for (int start = 0; start < P; start += kCompactThreads) {
-    const int i = start + tid;
-    const bool on = (i < P) && (mask[i] != 0);
-    const unsigned long long b = __ballot(on);
-    const int rank = __popcll(b & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_tot[wv] = __popcll(b);
+  for (int start = 0; start < P; start += kCompactThreads * V) {
+    const int i0 = start + tid * V;
+    unsigned on = 0;                           // bit b: cell i0 + b is active
+    if constexpr (V == 8) {
+      if (i0 + 8 <= P) {
+        const unsigned long long q = *reinterpret_cast<const unsigned long long*>(mask + i0);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) on |= ((q >> (8 * b)) & 0xffull) != 0 ? (1u << b) : 0u;
+      } else {
+        for (int b = 0; b < 8; ++b)
+          if (i0 + b < P && mask[i0 + b] != 0) on |= 1u << b;
+      }
+    } else {
+      on = (i0 < P && mask[i0] != 0) ? 1u : 0u;
+    }
+    const int c = __popc(on);
+    int incl = c;                              // inclusive scan over the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += t;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
     __syncthreads();
     int before = 0, total = 0;
 #pragma unroll
@@ -95,7 +169,12 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
       before += (k < wv) ? t : 0;
       total += t;
     }
-    if (on) idx[base + before + rank] = i;
+    int pos = base + before + incl - c;
+    while (on) {
+      const int b = __ffs(on) - 1;
+      idx[pos++] = i0 + b;
+      on &= on - 1;
+    }
     base += total;
     __syncthreads();                           // wave_tot is rewritten next round
   }
@@ -112,21 +191,29 @@ hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int 
   const size_t esz = x.dtype == LASNET_BF16 ? 2 : 4;
   const bool vec = ((size_t)x.c * esz) % 16 == 0 && ((uintptr_t)x.data % 16) == 0 &&
                    ((uintptr_t)Wm % 16) == 0 && (x.c % 8 == 0);
-#define LASNET_MASKER_LAUNCH(T, VEC)                                                          \
-  hipLaunchKernelGGL((masker_logit_kernel<T, VEC>), grid, block, 0, st, (const T*)x.data, Wm, \
-                     (double)bm, (double)thr, S, x.h, x.w, x.c, G, GW, P, mask, logits)
+  const bool hoist = vec && (size_t)S * x.c * esz == 4096;   // one group of four pieces per patch row
+#define LASNET_MASKER_LAUNCH(T, VEC, HOIST)                                                   \
+  hipLaunchKernelGGL((masker_logit_kernel<T, VEC, HOIST>), grid, block, 0, st, (const T*)x.data, \
+                     Wm, (double)bm, (double)thr, S, x.h, x.w, x.c, G, GW, P, mask, logits)
   if (P == 0) {
     // empty batch: nothing to pool; the compaction below still writes count = 0
   } else if (x.dtype == LASNET_BF16) {
-    if (vec) LASNET_MASKER_LAUNCH(uint16_t, true); else LASNET_MASKER_LAUNCH(uint16_t, false);
+    if (hoist) LASNET_MASKER_LAUNCH(uint16_t, true, true);
+    else if (vec) LASNET_MASKER_LAUNCH(uint16_t, true, false);
+    else LASNET_MASKER_LAUNCH(uint16_t, false, false);
   } else {
-    if (vec) LASNET_MASKER_LAUNCH(float, true); else LASNET_MASKER_LAUNCH(float, false);
+    if (hoist) LASNET_MASKER_LAUNCH(float, true, true);
+    else if (vec) LASNET_MASKER_LAUNCH(float, true, false);
+    else LASNET_MASKER_LAUNCH(float, false, false);
   }
 #undef LASNET_MASKER_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (count) {
-    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, st, mask, P, idx, count);
+    if (((uintptr_t)mask % 8) == 0)
+      hipLaunchKernelGGL(compact_kernel<8>, dim3(1), dim3(kCompactThreads), 0, st, mask, P, idx, count);
+    else
+      hipLaunchKernelGGL(compact_kernel<1>, dim3(1), dim3(kCompactThreads), 0, st, mask, P, idx, count);
     e = hipGetLastError();
   }
   return e;

@@ -78,6 +78,25 @@ def test_masker_threshold_and_extremes():
         assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
 
 
+def test_masker_unaligned_mask_buffer_and_many_rounds():
+    """A mask buffer that is not 8-byte aligned takes the byte-wise compaction; P = 20000 cells
+    needs three rounds of the 8-cells-per-thread one."""
+    cfg = synth.BlockConfig("pixel_s1_20000", 5, 50, 80, 8, 8, 1, "bf16", 0.41, 25)
+    inp = synth.make_block_inputs(cfg)
+    k = int(round(cfg.r * cfg.P))
+    bm = U.calibrate(inp, k)
+    d = U.dev_inputs(inp)
+    mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+    for off in (0, 1):
+        buf = torch.zeros(cfg.P + 8, dtype=torch.uint8, device="cuda")
+        mask = buf[off:off + cfg.P].view(cfg.N, cfg.G, cfg.GW)
+        _, idx, count = B.lasnet_masker(d["x"], d["Wm"], bm, cfg.S, 0.0, mask=mask)
+        torch.cuda.synchronize()
+        assert int(count.item()) == count_o == k
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+        assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
+
+
 def test_masker_empty_batch():
     x = torch.zeros((0, 8, 8, 16), dtype=torch.bfloat16, device="cuda")
     Wm = torch.zeros(16, device="cuda")
