@@ -516,7 +516,11 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
   // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
+#ifdef LASNET_C3_NOUNROLL
+#pragma nounroll
+#else
 #pragma unroll
+#endif
   for (int pass = 0; pass < NPASS; ++pass) {
     const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
     // residual and bias are requested before the GEMM so that their latency hides behind it
@@ -580,7 +584,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 }
 
 template <class K>
-__global__ __launch_bounds__(K::NT) void fused_bneck_kernel(
+__global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves per SIMD: at most 256 registers
     Geom g, int tile_slots, const __bf16* __restrict__ x, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ count, const __bf16* __restrict__ W1,
     const float* __restrict__ b1, const __bf16* __restrict__ W2, const float* __restrict__ b2,
@@ -767,11 +771,22 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const __bf16* __restr
 //             C     M   S PPW R1MAX NW KC NSTG conv1  conv2 RD2  conv3 NB3 RD3
 using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // ResNet-101 stage 3, S=2
 using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // stage 3, S=7 (also the dense tile)
+#ifdef LASNET_BIGWG
 using K_s2 = Cfg<512, 128, 4, 8, 224, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;     // stage 2, S=4
 using K_s2s7 = Cfg<512, 128, 7, 2, 192, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;   // stage 2, S=7 (dense tile)
 using K_s1 = Cfg<256, 64, 8, 2, 224, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;       // stage 1, S=8
 using K_s1s4 = Cfg<256, 64, 4, 6, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=4 (Table 1 block)
 using K_s1s7 = Cfg<256, 64, 7, 2, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=7 (dense tile)
+#else
+// Stages 1 and 2 have small weights (0.14 / 0.56 MB) and large maps: two 4-wave workgroups per
+// CU (<= 80 KB of LDS each), so that one workgroup's HBM-bound conv1 overlaps the other's
+// matrix work, instead of one 8-wave workgroup whose phases leave HBM or the matrix cores idle.
+using K_s2 = Cfg<512, 128, 4, 4, 112, 4, 64, 3, 1, 4, 1, 4, 12, 1, 4, 4, 4>;     // stage 2, S=4
+using K_s2s7 = Cfg<512, 128, 7, 1, 96, 4, 64, 3, 1, 4, 1, 4, 12, 1, 4, 4, 4>;    // stage 2, S=7 (dense tile)
+using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;       // stage 1, S=8
+using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // stage 1, S=4 (Table 1 block)
+using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // stage 1, S=7 (dense tile)
+#endif
 
 #define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
 
