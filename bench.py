@@ -2,9 +2,10 @@
 """Benchmark of the LASNet sparse-bottleneck hot path on one MI355X.
 
 One "step" = the whole path over one synthetic batch that is already resident in HBM:
-lasnet_masker (pool -> logit -> threshold -> index list) followed by
-lasnet_sparse_bottleneck (identity copy, gather + conv1 / conv3x3 / conv3 + scatter-add),
-with the active-patch count staying on the device.  Default workload: ResNet-101 stage-3
+lasnet_masker_ex (pool -> logit -> threshold -> index list, inactive cells passed through to
+out) followed by lasnet_sparse_bottleneck_ex (gather + conv1 / conv3x3 / conv3 + scatter-add
+on the active cells), with the active-patch count staying on the device.  Every element of
+out is written in every step.  Default workload: ResNet-101 stage-3
 bottleneck, 14x14x1024, mid 256, S=2, batch 128, bf16, masker calibrated to r = 0.5.
 
 Prints ONE JSON line: whole-job images/s, plus
@@ -97,6 +98,11 @@ def main():
 
     def step(i):
         x, out = xs[i % nbuf], outs[i % nbuf]
+        B.lasnet_masker_ex(x, d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count, pass_out=out)
+        B.lasnet_sparse_bottleneck(x, idx, count, S, *w, out=out, flags=B.LASNET_SKIP_IDENTITY)
+
+    def step_separate_copy(i):       # the two spec calls as they are: identity copy inside the block call
+        x, out = xs[i % nbuf], outs[i % nbuf]
         B.lasnet_masker(x, d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count)
         B.lasnet_sparse_bottleneck(x, idx, count, S, *w, out=out)
 
@@ -106,8 +112,9 @@ def main():
 
     def step_packed(i):
         x, out = xs[i % nbuf], outs[i % nbuf]
-        B.lasnet_masker(x, d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count)
-        B.lasnet_sparse_bottleneck_packed(x, idx, count, S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out=out)
+        B.lasnet_masker_ex(x, d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count, pass_out=out)
+        B.lasnet_sparse_bottleneck_packed(x, idx, count, S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out=out,
+                                          flags=B.LASNET_SKIP_IDENTITY)
 
     def run_steps(fn):
         for i in range(args.warmup):
@@ -120,6 +127,7 @@ def main():
         return time.perf_counter() - t0
 
     dt_packed = run_steps(step_packed) if packed is not None else None
+    dt_separate = run_steps(step_separate_copy)
     dt = run_steps(step)
     ms_per_step = dt / args.steps * 1e3
     images_per_s = cfg.N * args.steps / dt
@@ -148,6 +156,8 @@ def main():
                                                              flags=B.LASNET_SKIP_IDENTITY), reps)
     block_t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf]), reps)
     masker_t = timed(lambda i: B.lasnet_masker(xs[i % nbuf], d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count), reps)
+    masker_ex_t = timed(lambda i: B.lasnet_masker_ex(xs[i % nbuf], d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count,
+                                                     pass_out=outs[i % nbuf]), reps)
     dense_t = timed(lambda i: B.lasnet_dense_bottleneck(xs[i % nbuf], *w, out=outs[i % nbuf]), reps)
 
     torch_dense = None
@@ -201,7 +211,7 @@ def main():
         cpu = cpu_baseline(cfg, inp, bm)
 
     result = {
-        "metric": "sparse bottleneck images/s at r=%.2g (masker + index list + fused block)" % cfg.r,
+        "metric": "sparse bottleneck images/s at r=%.2g (masker + index list + identity pass-through + fused block)" % cfg.r,
         "value": images_per_s,
         "unit": "images/s",
         "n_gpus": 1,
@@ -220,8 +230,12 @@ def main():
         "prepacked_weights": None if dt_packed is None else {
             "ms_per_step": dt_packed / args.steps * 1e3, "images_per_s": cfg.N * args.steps / dt_packed,
             "note": "same step through lasnet_sparse_bottleneck_packed (weights repacked once, outside the loop)"},
+        "separate_identity_copy": {
+            "ms_per_step": dt_separate / args.steps * 1e3, "images_per_s": cfg.N * args.steps / dt_separate,
+            "note": "lasnet_masker + lasnet_sparse_bottleneck: the block call copies x to out before the fused kernel"},
         "speedup_vs_dense": dense_best / block_t["mean_ms"],
-        "kernels_ms": {"masker+compaction": masker_t, "pack+copy+fused_block": block_t, "fused_block": fused_t,
+        "kernels_ms": {"masker+compaction": masker_t, "masker+identity+compaction": masker_ex_t,
+                       "pack+copy+fused_block": block_t, "fused_block": fused_t,
                        "dense_own": dense_t, "dense_torch_miopen": torch_dense},
         "hbm_floor_ms": 2 * x_bytes / (PEAK_HBM_GBS * 1e9) * 1e3,
         "roofline": {"bound": "mfma", "kernel": "fused_bneck_kernel", "achieved": achieved_tflops,

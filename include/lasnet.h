@@ -84,6 +84,19 @@ LASNET_API const char* lasnet_status_string(int status); /* host pointer to a st
 LASNET_API int lasnet_masker(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
                   uint8_t* mask, int32_t* idx, int32_t* count, void* hip_stream);
 
+/*
+ * lasnet_masker with the identity pass-through fused in (Sec. 3.1: positions that are not
+ * selected keep the block input; Sec. 3.4 fuses memory-bound operators that share an input --
+ * the masker already reads every cell of x).  pass_out: NULL (then exactly lasnet_masker), or
+ * a feature map of x's shape and dtype in a different buffer (same buffer: LASNET_EALIAS): every
+ * cell whose mask comes out 0 is copied, bit for bit, from x to pass_out; active cells of
+ * pass_out are not touched.  Follow with lasnet_sparse_bottleneck_ex / _packed on the same
+ * out with LASNET_SKIP_IDENTITY: together they write every element of out exactly once.
+ */
+LASNET_API int lasnet_masker_ex(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
+                     uint8_t* mask, int32_t* idx, int32_t* count, lasnet_tensor* pass_out,
+                     void* hip_stream);
+
 /* The same fp64 logits as lasnet_masker compares, written out: logits [N*G*GW] double.
  * For calibrating bm/thr on synthetic inputs and for debugging a mask. */
 LASNET_API int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, float bm, int S,

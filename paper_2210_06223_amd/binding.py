@@ -21,7 +21,7 @@ LASNET_POST_RELU, LASNET_FORCE_GENERIC, LASNET_SKIP_IDENTITY = 1, 2, 4
 LASNET_OK, LASNET_EINVAL, LASNET_ESHAPE, LASNET_EUNSUPPORTED, LASNET_EALIAS, LASNET_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = (
-    "lasnet_version", "lasnet_status_string", "lasnet_masker", "lasnet_masker_logits",
+    "lasnet_version", "lasnet_status_string", "lasnet_masker", "lasnet_masker_ex", "lasnet_masker_logits",
     "lasnet_sparse_bottleneck", "lasnet_sparse_bottleneck_ex", "lasnet_dense_bottleneck",
     "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
     "lasnet_sparse_bottleneck_packed",
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.lasnet_status_string.argtypes = [ip]
         L.lasnet_masker.restype = ip
         L.lasnet_masker.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, vp]
+        L.lasnet_masker_ex.restype = ip
+        L.lasnet_masker_ex.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, tp, vp]
         L.lasnet_masker_logits.restype = ip
         L.lasnet_masker_logits.argtypes = [tp, vp, ctypes.c_float, ip, vp, vp]
         L.lasnet_sparse_bottleneck.restype = ip
@@ -140,6 +142,32 @@ def lasnet_masker(x: torch.Tensor, Wm: torch.Tensor, bm: float, S: int, thr: flo
     st = lib().lasnet_masker(ctypes.byref(d), _ptr(_f32(Wm, "Wm")), float(bm), int(S), float(thr),
                              _ptr(mask), _ptr(idx), _ptr(count), _stream(stream))
     _check(st, "lasnet_masker")
+    return mask, idx, count
+
+
+def lasnet_masker_ex(x: torch.Tensor, Wm: torch.Tensor, bm: float, S: int, thr: float = 0.0,
+                     mask: Optional[torch.Tensor] = None, idx: Optional[torch.Tensor] = None,
+                     count: Optional[torch.Tensor] = None, pass_out: Optional[torch.Tensor] = None,
+                     stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """lasnet_masker that also copies every inactive cell of x to pass_out (may be None)."""
+    d = _as_tensor_desc(x)
+    N, H, W, _ = x.shape
+    if S <= 0 or H % S or W % S:
+        _check(LASNET_ESHAPE if S > 0 else LASNET_EINVAL, "lasnet_masker_ex")
+    G, GW = H // S, W // S
+    if mask is None:
+        mask = torch.empty((N, G, GW), dtype=torch.uint8, device=x.device)
+    if idx is None:
+        idx = torch.empty((N * G * GW,), dtype=torch.int32, device=x.device)
+    if count is None:
+        count = torch.empty((1,), dtype=torch.int32, device=x.device)
+    po = None
+    if pass_out is not None:
+        po = _as_tensor_desc(pass_out)
+    st = lib().lasnet_masker_ex(ctypes.byref(d), _ptr(_f32(Wm, "Wm")), float(bm), int(S), float(thr),
+                                _ptr(mask), _ptr(idx), _ptr(count),
+                                ctypes.byref(po) if po is not None else None, _stream(stream))
+    _check(st, "lasnet_masker_ex")
     return mask, idx, count
 
 

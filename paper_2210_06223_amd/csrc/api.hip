@@ -127,14 +127,24 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
 }
 
 int masker_common(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
-                  uint8_t* mask, int32_t* idx, int32_t* count, double* logits, void* stream) {
+                  uint8_t* mask, int32_t* idx, int32_t* count, double* logits,
+                  const lasnet_tensor* pass_out, void* stream) {
   int s = check_tensor(x);
   if (s != LASNET_OK) return s;
   if (!Wm) return LASNET_EINVAL;
   if (S <= 0) return LASNET_EINVAL;
   if (x->h % S != 0 || x->w % S != 0) return LASNET_ESHAPE;
+  if (pass_out) {
+    s = check_tensor(pass_out);
+    if (s != LASNET_OK) return s;
+    if (pass_out->n != x->n || pass_out->h != x->h || pass_out->w != x->w || pass_out->c != x->c ||
+        pass_out->dtype != x->dtype)
+      return LASNET_ESHAPE;
+    if (x->n > 0 && pass_out->data == x->data) return LASNET_EALIAS;
+  }
   if (!device_ok()) return LASNET_EHIP;
-  const hipError_t e = launch_masker(*x, Wm, bm, S, thr, mask, idx, count, logits, (hipStream_t)stream);
+  const hipError_t e = launch_masker(*x, Wm, bm, S, thr, mask, idx, count, logits,
+                                     pass_out ? pass_out->data : nullptr, (hipStream_t)stream);
   return e == hipSuccess ? LASNET_OK : LASNET_EHIP;
 }
 
@@ -161,13 +171,22 @@ int lasnet_masker(const lasnet_tensor* x, const float* Wm, float bm, int S, floa
   if (!count) return LASNET_EINVAL;
   const bool empty = x && x->n == 0;            // an empty batch has no mask or idx storage
   if (!empty && (!mask || !idx)) return LASNET_EINVAL;
-  return masker_common(x, Wm, bm, S, thr, mask, idx, count, nullptr, hip_stream);
+  return masker_common(x, Wm, bm, S, thr, mask, idx, count, nullptr, nullptr, hip_stream);
+}
+
+int lasnet_masker_ex(const lasnet_tensor* x, const float* Wm, float bm, int S, float thr,
+                     uint8_t* mask, int32_t* idx, int32_t* count, lasnet_tensor* pass_out,
+                     void* hip_stream) {
+  if (!count) return LASNET_EINVAL;
+  const bool empty = x && x->n == 0;
+  if (!empty && (!mask || !idx)) return LASNET_EINVAL;
+  return masker_common(x, Wm, bm, S, thr, mask, idx, count, nullptr, pass_out, hip_stream);
 }
 
 int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, float bm, int S, double* logits,
                          void* hip_stream) {
   if (!logits) return LASNET_EINVAL;
-  return masker_common(x, Wm, bm, S, 0.f, nullptr, nullptr, nullptr, logits, hip_stream);
+  return masker_common(x, Wm, bm, S, 0.f, nullptr, nullptr, nullptr, logits, nullptr, hip_stream);
 }
 
 int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,

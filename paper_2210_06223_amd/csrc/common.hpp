@@ -28,7 +28,7 @@ struct BlockWeights {
 // ---- launchers (each returns a hipError_t from the launch, never synchronises) ----
 hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int S, float thr,
                          uint8_t* mask, int32_t* idx, int32_t* count, double* logits,
-                         hipStream_t st);
+                         void* pass_out, hipStream_t st);
 
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 

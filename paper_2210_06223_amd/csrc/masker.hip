@@ -46,7 +46,8 @@ __device__ inline void fma_piece(double& acc, const uint4& q, const float4& w0, 
 template <typename T, bool VEC, bool HOIST>
 __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
     const T* __restrict__ x, const float* __restrict__ Wm, double bm, double thr, int S, int H,
-    int W, int C, int G, int GW, int P, uint8_t* __restrict__ mask, double* __restrict__ logits) {
+    int W, int C, int G, int GW, int P, uint8_t* __restrict__ mask, double* __restrict__ logits,
+    T* __restrict__ pass_out) {
   const int lane = threadIdx.x & 63;
   const int cell = blockIdx.x * kCellsPerBlock + (threadIdx.x >> 6);
   if (cell >= P) return;                      // wave-uniform
@@ -116,11 +117,36 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
       }
     }
   }
+  // the butterfly leaves the same bits in every lane (a + b == b + a), so the decision is wave-uniform
   const double acc = wave_sum((acc0 + acc1) + (acc2 + acc3));
+  const double logit = bm + acc / (double)(S * S);
+  const bool on = logit > thr;
   if (lane == 0) {
-    const double logit = bm + acc / (double)(S * S);
     if (logits) logits[cell] = logit;
-    if (mask) mask[cell] = logit > thr ? 1 : 0;
+    if (mask) mask[cell] = on ? 1 : 0;
+  }
+  // Identity pass-through fused into the masker (Sec. 3.1: positions that are not selected keep
+  // the input): a cell that stays inactive is copied now, while its rows are still in cache.
+  if (pass_out != nullptr && !on) {
+    T* out0 = pass_out + (cell0 - x);
+    for (int i = 0; i < S; ++i) {
+      const T* row = cell0 + i * pitch;
+      T* orow = out0 + i * pitch;
+      if constexpr (VEC) {
+        constexpr int V = 16 / (int)sizeof(T);
+        int e = lane * V;
+        for (; e + 3 * 64 * V < seg; e += 4 * 64 * V) {
+          uint4 q[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4*>(row + e + u * 64 * V);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(orow + e + u * 64 * V) = q[u];
+        }
+        for (; e < seg; e += 64 * V) *reinterpret_cast<uint4*>(orow + e) = *reinterpret_cast<const uint4*>(row + e);
+      } else {
+        for (int e = lane; e < seg; e += 64) orow[e] = row[e];
+      }
+    }
   }
 }
 
@@ -185,16 +211,17 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 
 hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int S, float thr,
                          uint8_t* mask, int32_t* idx, int32_t* count, double* logits,
-                         hipStream_t st) {
+                         void* pass_out, hipStream_t st) {
   const int G = x.h / S, GW = x.w / S, P = x.n * G * GW;
   const dim3 grid(P > 0 ? (P + kCellsPerBlock - 1) / kCellsPerBlock : 1), block(kMaskerThreads);
   const size_t esz = x.dtype == LASNET_BF16 ? 2 : 4;
   const bool vec = ((size_t)x.c * esz) % 16 == 0 && ((uintptr_t)x.data % 16) == 0 &&
-                   ((uintptr_t)Wm % 16) == 0 && (x.c % 8 == 0);
+                   ((uintptr_t)Wm % 16) == 0 && (x.c % 8 == 0) && ((uintptr_t)pass_out % 16) == 0;
   const bool hoist = vec && (size_t)S * x.c * esz == 4096;   // one group of four pieces per patch row
 #define LASNET_MASKER_LAUNCH(T, VEC, HOIST)                                                   \
   hipLaunchKernelGGL((masker_logit_kernel<T, VEC, HOIST>), grid, block, 0, st, (const T*)x.data, \
-                     Wm, (double)bm, (double)thr, S, x.h, x.w, x.c, G, GW, P, mask, logits)
+                     Wm, (double)bm, (double)thr, S, x.h, x.w, x.c, G, GW, P, mask, logits,      \
+                     (T*)pass_out)
   if (P == 0) {
     // empty batch: nothing to pool; the compaction below still writes count = 0
   } else if (x.dtype == LASNET_BF16) {

@@ -46,6 +46,12 @@ def test_masker_argument_errors():
     bad = _t(dtype=7)
     assert call(ctypes.byref(bad), p, 2) == B.LASNET_EINVAL
     assert L.lasnet_masker_logits(ctypes.byref(x), p, 0.0, 2, None, None) == B.LASNET_EINVAL
+    # fused identity pass-through: the destination must match x and be another buffer
+    ex = lambda po: L.lasnet_masker_ex(ctypes.byref(x), p, 0.0, 2, 0.0, p, p, p, ctypes.byref(po), None)
+    assert ex(_t(data=0x1000)) == B.LASNET_EALIAS
+    assert ex(_t(data=0x9000, c=32)) == B.LASNET_ESHAPE
+    assert ex(_t(data=0x9000, dtype=B.LASNET_BF16)) == B.LASNET_ESHAPE
+    assert ex(_t(data=0)) == B.LASNET_EINVAL
 
 
 def test_block_argument_errors():

@@ -97,6 +97,46 @@ def test_masker_unaligned_mask_buffer_and_many_rounds():
         assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
 
 
+MASKER_EX_CASES = [
+    _cfg("stage3_b128", N=3, name="s3_ex"),        # matrix-core block kernel, hoisted masker path
+    _cfg("stage2_b128", N=2, name="s2_ex"),
+    _cfg("stage1_b64", N=1, name="s1_ex"),
+    _cfg("tiny_f32"),                              # fp32, generic block kernel
+    synth.BlockConfig("odd_c20_s3_f32_ex", 2, 6, 9, 20, 12, 3, "f32", 0.5, 26),     # scalar masker path
+    synth.BlockConfig("odd_c24_s2_bf16_ex", 3, 4, 6, 24, 8, 2, "bf16", 0.4, 27),    # 16-byte pieces, ragged groups
+]
+
+
+@pytest.mark.parametrize("cfg", MASKER_EX_CASES, ids=lambda c: c.name)
+def test_masker_with_fused_identity_then_block_without_copy(cfg):
+    """lasnet_masker_ex copies the inactive cells, lasnet_sparse_bottleneck_ex(SKIP_IDENTITY) writes the
+    active ones: together every element of a poisoned out, against the oracle."""
+    _say("masker_ex", cfg)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    for k in (int(round(cfg.r * cfg.P)), 0, cfg.P):
+        bm = U.calibrate(inp, k)
+        mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+        out = torch.full_like(d["x"], 768.0)                               # exact in bf16
+        mask, idx, count = B.lasnet_masker_ex(d["x"], d["Wm"], bm, cfg.S, 0.0, pass_out=out)
+        torch.cuda.synchronize()
+        assert int(count.item()) == count_o == k
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+        assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
+        up = np.broadcast_to(O.upsample_mask(mask_o, cfg.S)[..., None].astype(bool), tuple(d["x"].shape))
+        o = U.to_f64(out)
+        assert np.array_equal(U.bits(out)[~up], U.bits(d["x"])[~up])      # inactive cells: x, bit for bit
+        assert (o[up] == 768.0).all()                                      # active cells: not touched
+        B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), out=out,
+                                   flags=B.LASNET_SKIP_IDENTITY)
+        torch.cuda.synchronize()
+        ref = O.sparse_bottleneck(inp.f64["x"], mask_o, cfg.S, *_oracle_w(inp))
+        U.assert_block_close(out, ref, d["x"], up, cfg.dtype, cfg.name)
+    with pytest.raises(B.LasnetError) as e:
+        B.lasnet_masker_ex(d["x"], d["Wm"], 0.0, cfg.S, 0.0, pass_out=d["x"])
+    assert e.value.status == B.LASNET_EALIAS
+
+
 def test_masker_empty_batch():
     x = torch.zeros((0, 8, 8, 16), dtype=torch.bfloat16, device="cuda")
     Wm = torch.zeros(16, device="cuda")
