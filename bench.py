@@ -30,9 +30,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (summaries under profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per launch of the fused kernel between L2 and the memory side, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's
+# plain copy kernel of known size (profiles/bench_stage3_b128_hbm_traffic_pmc.txt).
+MEASURED_TRAFFIC_BYTES = {"stage3_b128": 140906312}
 
 
 def parse_args():

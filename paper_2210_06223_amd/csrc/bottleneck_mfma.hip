@@ -145,8 +145,12 @@ __device__ __forceinline__ FragRow frag_row(int row, int ld, int lg, int key, in
   return FragRow{row * ld * 2, (lg ^ (key & mask)) << 4};
 }
 __device__ __forceinline__ bf16x8 frag_read(const AS_LDS __bf16* base, FragRow r, int s) {
+  int key = r.key_bytes;
+  // opaque to the optimiser: otherwise (64*s) ^ key is computed for every s ahead of the loop,
+  // kept in registers across the whole phase, and some of them end up spilled
+  asm volatile("" : "+v"(key));
   return *reinterpret_cast<const AS_LDS bf16x8*>(reinterpret_cast<const AS_LDS char*>(base) + r.row_bytes +
-                                                 ((64 * s) ^ r.key_bytes));
+                                                 ((64 * s) ^ key));
 }
 
 // Which output channel a lane holds.  In the 16x16 result of an MFMA, lane group lg (= lane / 16)
@@ -576,7 +580,9 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
               o[h * 4 + v] = (__bf16)r;
             }
           }
-          *reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + lane_channel(chb, NB, j, lg, 0)) = o;
+          // streaming store: out is not read again here, and lines left dirty in L2 would all be
+          // written back in one burst when the kernel ends
+          __builtin_nontemporal_store(o, reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + lane_channel(chb, NB, j, lg, 0)));
         }
       }
     }

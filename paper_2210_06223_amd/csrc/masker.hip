@@ -17,6 +17,12 @@ __device__ inline double wave_sum(double v) {
 
 __device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
+// 16-byte streaming store (the destination is not read again by this kernel)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void store_nt16(void* p, const uint4& q) {
+  __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(p));
+}
+
 // acc += sum over the V elements of one 16-byte piece of x times their masker weights.
 __device__ inline void fma_piece(double& acc, const uint4& q, const float4& w0, const float4& w1,
                                  uint16_t /*bf16 tag*/) {
@@ -69,7 +75,23 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
         w[u][0] = *reinterpret_cast<const float4*>(Wm + c);
         w[u][1] = V == 8 ? *reinterpret_cast<const float4*>(Wm + c + 4) : float4{0.f, 0.f, 0.f, 0.f};
       }
-      for (int i = 0; i < S; ++i) {
+      int i = 0;
+      for (; i + 2 <= S; i += 2) {            // two rows = eight pieces in flight per lane
+        const T* row = cell0 + i * pitch;
+        uint4 q[2][4];
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int u = 0; u < 4; ++u) q[r][u] = *reinterpret_cast<const uint4*>(row + r * pitch + (lane + 64 * u) * V);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          fma_piece(acc0, q[r][0], w[0][0], w[0][1], T{});
+          fma_piece(acc1, q[r][1], w[1][0], w[1][1], T{});
+          fma_piece(acc2, q[r][2], w[2][0], w[2][1], T{});
+          fma_piece(acc3, q[r][3], w[3][0], w[3][1], T{});
+        }
+      }
+      for (; i < S; ++i) {
         const T* row = cell0 + i * pitch;
         uint4 q[4];
 #pragma unroll
@@ -129,21 +151,40 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
   // the input): a cell that stays inactive is copied now, while its rows are still in cache.
   if (pass_out != nullptr && !on) {
     T* out0 = pass_out + (cell0 - x);
-    for (int i = 0; i < S; ++i) {
-      const T* row = cell0 + i * pitch;
-      T* orow = out0 + i * pitch;
-      if constexpr (VEC) {
-        constexpr int V = 16 / (int)sizeof(T);
+    if constexpr (VEC) {
+      constexpr int V = 16 / (int)sizeof(T);
+      constexpr int GRP = 4 * 64 * V;
+      for (int i = 0; i < S; ++i) {
+        const T* row = cell0 + i * pitch;
+        T* orow = out0 + i * pitch;
         int e = lane * V;
-        for (; e + 3 * 64 * V < seg; e += 4 * 64 * V) {
+        if (HOIST && i + 2 <= S) {            // two whole rows = eight pieces in flight per lane
+          uint4 q[2][4];
+#pragma unroll
+          for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[r][u] = *reinterpret_cast<const uint4*>(row + r * pitch + e + u * 64 * V);
+#pragma unroll
+          for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              store_nt16(orow + r * pitch + e + u * 64 * V, q[r][u]);
+          ++i;
+          continue;
+        }
+        for (; e + GRP - 64 * V < seg; e += GRP) {
           uint4 q[4];
 #pragma unroll
           for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const uint4*>(row + e + u * 64 * V);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(orow + e + u * 64 * V) = q[u];
+          for (int u = 0; u < 4; ++u) store_nt16(orow + e + u * 64 * V, q[u]);
         }
         for (; e < seg; e += 64 * V) *reinterpret_cast<uint4*>(orow + e) = *reinterpret_cast<const uint4*>(row + e);
-      } else {
+      }
+    } else {
+      for (int i = 0; i < S; ++i) {
+        const T* row = cell0 + i * pitch;
+        T* orow = out0 + i * pitch;
         for (int e = lane; e < seg; e += 64) orow[e] = row[e];
       }
     }
