@@ -146,6 +146,19 @@ def main():
         return {"mean_ms": float(np.mean(t)), "median_ms": t[len(t) // 2], "p10_ms": t[len(t) // 10],
                 "p90_ms": t[(len(t) * 9) // 10]}
 
+    def timed_loop(fn, n):
+        """Mean duration of n back-to-back calls (one event pair around all of them), in ms."""
+        for i in range(5):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
     reps = max(20, min(args.steps, 200))
     # the fused kernel alone: same launch as inside the step, identity copy skipped (outs already hold x)
     if packed is not None:
@@ -155,11 +168,27 @@ def main():
     else:
         fused_t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf],
                                                              flags=B.LASNET_SKIP_IDENTITY), reps)
+    if packed is not None:
+        fused_loop_ms = timed_loop(lambda i: B.lasnet_sparse_bottleneck_packed(
+            xs[i % nbuf], idx, count, S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out=outs[i % nbuf],
+            flags=B.LASNET_SKIP_IDENTITY), reps)
+    else:
+        fused_loop_ms = timed_loop(lambda i: B.lasnet_sparse_bottleneck(
+            xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf], flags=B.LASNET_SKIP_IDENTITY), reps)
     block_t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx, count, S, *w, out=outs[i % nbuf]), reps)
     masker_t = timed(lambda i: B.lasnet_masker(xs[i % nbuf], d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count), reps)
     masker_ex_t = timed(lambda i: B.lasnet_masker_ex(xs[i % nbuf], d["Wm"], bm, S, 0.0, mask=mask, idx=idx, count=count,
                                                      pass_out=outs[i % nbuf]), reps)
     dense_t = timed(lambda i: B.lasnet_dense_bottleneck(xs[i % nbuf], *w, out=outs[i % nbuf]), reps)
+    # the dense block through the prepacked entry: every cell active (idx = NULL) on the tile side that
+    # lasnet_dense_bottleneck picks (the largest built S that divides H and W)
+    dense_packed_ms = None
+    if packed is not None:
+        S_dense = max(s_ for s_ in range(1, 17) if cfg.H % s_ == 0 and cfg.W % s_ == 0
+                      and B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, s_) == 1)
+        packed_dense = B.lasnet_pack_weights(S_dense, d["W1"], d["W2"], d["W3"])
+        dense_packed_ms = timed_loop(lambda i: B.lasnet_sparse_bottleneck_packed(
+            xs[i % nbuf], None, None, S_dense, cfg.M, packed_dense, d["b1"], d["b2"], d["b3"], out=outs[i % nbuf]), reps)
 
     torch_dense = None
     if not args.no_torch_dense and cfg.dtype == "bf16":
@@ -186,26 +215,37 @@ def main():
 
     flops_img = cfg.H * cfg.W * (2 * cfg.C * cfg.M + 18 * cfg.M * cfg.M + 2 * cfg.M * cfg.C)
     active_flops = n_active * S * S * (flops_img / (cfg.H * cfg.W))
-    fused_s = fused_t["mean_ms"] * 1e-3
+    fused_s = fused_loop_ms * 1e-3             # average launch duration over `reps` back-to-back launches
     achieved_tflops = active_flops / fused_s / 1e12
     esize = 2 if cfg.dtype == "bf16" else 4
     x_bytes = cfg.N * cfg.H * cfg.W * cfg.C * esize
-    dense_best = dense_t["mean_ms"]
+    dense_best = dense_t["mean_ms"] if dense_packed_ms is None else dense_packed_ms
     if torch_dense and "mean_ms" in torch_dense:
         dense_best = min(dense_best, torch_dense["mean_ms"])
 
     sweep = None
     if args.sweep:
+        # latency against the activation ratio (index lists fed directly; per-image ratios Beta-distributed
+        # around the mean): block = pack + fused kernel on the active cells (the inactive ones are the
+        # masker's pass-through, not in this call), against the dense block through the same entry style
         sweep = []
+        dense_loop = timed_loop(lambda i: B.lasnet_dense_bottleneck(xs[i % nbuf], *w, out=outs[i % nbuf]), 50)
+        if torch_dense and "mean_ms" in torch_dense:
+            dense_loop = min(dense_loop, torch_dense["mean_ms"])
         for r in (0.1, 0.25, 0.5, 0.75, 1.0):
             for structure in ("iid", "blob"):
                 il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, r, seed=cfg.seed, structure=structure)
                 idx_r = torch.zeros((P,), dtype=torch.int32, device=dev)
                 idx_r[: len(il)] = torch.from_numpy(il).to(dev)
                 cnt_r = torch.tensor([len(il)], dtype=torch.int32, device=dev)
-                t = timed(lambda i: B.lasnet_sparse_bottleneck(xs[i % nbuf], idx_r, cnt_r, S, *w, out=outs[i % nbuf]), reps)
-                sweep.append({"r_mean": r, "structure": structure, "active": len(il), "block_ms": t["mean_ms"],
-                              "latency_ratio_vs_dense": t["mean_ms"] / dense_best})
+                t_skip = timed_loop(lambda i: B.lasnet_sparse_bottleneck(
+                    xs[i % nbuf], idx_r, cnt_r, S, *w, out=outs[i % nbuf], flags=B.LASNET_SKIP_IDENTITY), 50)
+                t_copy = timed_loop(lambda i: B.lasnet_sparse_bottleneck(
+                    xs[i % nbuf], idx_r, cnt_r, S, *w, out=outs[i % nbuf]), 50)
+                sweep.append({"r_mean": r, "structure": structure, "active": len(il),
+                              "block_ms": t_skip, "block_with_identity_copy_ms": t_copy,
+                              "latency_ratio_vs_dense": t_skip / dense_loop})
+        sweep_note = {"dense_ms": dense_loop, "timing": "mean over 50 back-to-back launches between two events"}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -234,19 +274,24 @@ def main():
         "separate_identity_copy": {
             "ms_per_step": dt_separate / args.steps * 1e3, "images_per_s": cfg.N * args.steps / dt_separate,
             "note": "lasnet_masker + lasnet_sparse_bottleneck: the block call copies x to out before the fused kernel"},
-        "speedup_vs_dense": dense_best / block_t["mean_ms"],
+        "speedup_vs_dense": dense_best / (fused_loop_ms if packed is not None else block_t["mean_ms"]),
+        "speedup_vs_dense_note": "dense block (the faster of the library's and torch/MIOpen's) / sparse block at this r, "
+                                 "both without the identity pass-through, which lives in the masker call",
         "kernels_ms": {"masker+compaction": masker_t, "masker+identity+compaction": masker_ex_t,
                        "pack+copy+fused_block": block_t, "fused_block": fused_t,
-                       "dense_own": dense_t, "dense_torch_miopen": torch_dense},
+                       "dense_own": dense_t, "dense_own_prepacked_loop_ms": dense_packed_ms,
+                       "fused_block_loop_ms": fused_loop_ms, "dense_torch_miopen": torch_dense},
         "hbm_floor_ms": 2 * x_bytes / (PEAK_HBM_GBS * 1e9) * 1e3,
         "roofline": {"bound": "mfma", "kernel": "fused_bneck_kernel", "achieved": achieved_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                     "active_flops_per_launch": active_flops, "avg_launch_ms": fused_t["mean_ms"]},
+                     "active_flops_per_launch": active_flops, "avg_launch_ms": fused_loop_ms,
+                     "avg_launch_ms_single_event_pairs": fused_t["mean_ms"], "launches_timed": reps},
         "cpu_baseline": cpu,
     }
     if sweep is not None:
         result["ratio_sweep"] = sweep
+        result["ratio_sweep_note"] = sweep_note
     print(json.dumps(result))
 
 

@@ -79,8 +79,9 @@ struct Cfg {
   static constexpr int R2B = roundup(cdiv(R2, 16), cmax(WR2, WR3)), R2P = R2B * 16;
   // LDS rows have power-of-two pitch and their 16-byte chunks are XOR-swizzled (see swz()):
   // measured on gfx950, ds_read_b128 then runs at ~6 clk per wave against ~9 with a padded pitch.
-  static constexpr int LDX = KC, LDY = M < 128 ? 128 : M;
+  static constexpr int LDX = KC, LDY = M;
   static constexpr int XMASK = KC / 8 - 1;
+  static constexpr int YMASK = LDY / 8 - 1 < 15 ? LDY / 8 - 1 : 15;   // swizzle key bits of a y1/y2 row
   static constexpr int MS = M / 32;                    // k-steps over the mid channels
   static constexpr int HT = pow2_at_least(2 * R1MAX);  // hash table slots
   // LDS map (bytes)
@@ -90,7 +91,8 @@ struct Cfg {
   static constexpr int OFF_ROWPIX = (OFF_WINROW + PPW * WW * 2 + 15) / 16 * 16;  // int[R1MAX]
   static constexpr int OFF_PIXQ = OFF_ROWPIX + R1MAX * 4;       // int  [R2P]
   static constexpr int OFF_MISC = OFF_PIXQ + R2P * 4;           // int  [4]
-  static constexpr int OFF_Y1 = (OFF_MISC + 16 + 15) / 16 * 16;
+  static constexpr int OFF_CELL = OFF_MISC + 16;                // int  [PPW]    cell ids of the batch
+  static constexpr int OFF_Y1 = (OFF_CELL + PPW * 4 + 15) / 16 * 16;
   static constexpr int Y1_BYTES = (R1MAX + 1) * LDY * 2;
   static constexpr int OFF_XS = OFF_Y1 + Y1_BYTES;
   static constexpr int STAGE_ELEMS = R1MAX * LDX;
@@ -105,7 +107,13 @@ struct Cfg {
   static_assert(M % (16 * WC1) == 0 && M % (16 * WC2) == 0 && C % (16 * WC3) == 0, "channel split");
   static_assert(NBT3 % NB3 == 0 && NB3 % 2 == 0, "conv3 passes; 16-byte epilogue pieces");
   static_assert(C % (2 * KC) == 0 && KC == 64 && M % 32 == 0, "k steps");
-  static_assert(NSTG == 3, "x stream: three LDS stages, two chunks in flight");
+  // x stream: chunk c lives in stage c % NSTG.  XD chunks are requested ahead of the one being
+  // consumed: all of them when they all fit, else one less than there are stages (a stage is
+  // refilled right after the barrier that follows its last read).
+  static constexpr int NCH = C / KC;
+  static constexpr int XD = NCH <= NSTG ? NCH : NSTG - 1;
+  static_assert(NSTG >= 3 && XD >= 2, "x stream depth");
+  static_assert(LDY % 64 == 0 && (LDY & (LDY - 1)) == 0, "y rows: power-of-two pitch, whole swizzle groups");
   static_assert((9 * MS) % RD2 == 0 && RD2 % MS == 0 && MS % RD3 == 0, "weight rings");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
@@ -195,6 +203,33 @@ template <int VM>
 __device__ __forceinline__ void barrier_keep_vm() {
   static_assert(VM >= 0 && VM < 64, "vmcnt is 6 bits");
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
+// The same with a count that is a constant only after unrolling (folds to one of the cases).
+template <int I = 63>
+__device__ __forceinline__ void barrier_keep_vm_n(int n) {
+  if (n >= I) barrier_keep_vm<I>();
+  else if constexpr (I > 0) barrier_keep_vm_n<I - 1>(n);
+}
+
+// conv1's stream of global-memory operations per wave, in program order (they complete in
+// order):  W(0) X(0) W(1) X(1) X(2) .. X(D-1) | chunk 0: W(2) X(D) | chunk 1: W(3) X(D+1) | ...
+// W(c) = the NWL weight fragments of chunk c, X(c) = the NXL x loads of chunk c, D = chunks
+// of x requested ahead.  The barrier that opens chunk ch needs W(ch) and X(ch) complete;
+// this is the number of operations issued after the younger of the two, which may stay in flight.
+constexpr int conv1_keep_in_flight(int ch, int nch, int d, int nwl, int nxl) {
+  int after_w = -1, after_x = -1;          // operations issued after W(ch) / after X(ch)
+  int total = 0;
+  auto issue = [&](bool is_w, int c, int n) {
+    if (c >= nch) return;
+    total += n;
+    if (c == ch) { if (is_w) after_w = total; else after_x = total; }
+  };
+  issue(true, 0, nwl); issue(false, 0, nxl); issue(true, 1, nwl);
+  for (int c = 1; c < d; ++c) issue(false, c, nxl);
+  for (int c = 0; c < ch; ++c) { issue(true, c + 2, nwl); issue(false, c + d, nxl); }
+  const int last = after_w > after_x ? after_w : after_x;
+  return total - last;
 }
 
 // A lane's 4*NB consecutive channels leave as 16-byte pieces (8 channels = one swizzle chunk).
@@ -296,11 +331,8 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
     for (int s = 0; s < KS; ++s) boff[i][s] = swz(row, K::LDX, s * 4 + lg, row, K::XMASK);
   }
 
-  // Order of a wave's global-memory operations (they complete in order):
-  //   W(0) X(0) W(1) X(1) | chunk 0: W(2) X(2) | chunk 1: W(3) X(3) | ...
-  // (W(c): the NWL weight fragments of chunk c, X(c): the NXL x loads of chunk c).  At the
-  // barrier that opens chunk ch, everything up to X(ch) has to be there, and what was issued
-  // after it is exactly W(ch+1) X(ch+1): NWL + NXL operations may stay in flight.
+  // prologue of the stream (see conv1_keep_in_flight for the order)
+  constexpr int XD = K::XD;
 #pragma unroll
   for (int t = 0; t < KS; ++t) wload(t, t);
   __builtin_amdgcn_sched_barrier(0);
@@ -309,7 +341,8 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
 #pragma unroll
   for (int t = KS; t < 2 * KS; ++t) wload(t, t);
   __builtin_amdgcn_sched_barrier(0);
-  issue_x(1);
+#pragma unroll
+  for (int c = 1; c < XD; ++c) issue_x(c);
   __builtin_amdgcn_sched_barrier(0);
 
   // B fragments are read one k-step ahead of the MFMAs that use them (bcur/bnxt), so a
@@ -322,11 +355,8 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const int ch = ch2 + cc;
-#if (LASNET_X1 & 2)
-      if (ch == 0 || ch + 1 == NCH) { if (ch + 1 < NCH) barrier_keep_vm<NXL + NWL>(); else barrier_keep_vm<0>(); }
-#else
-      if (ch + 1 < NCH) barrier_keep_vm<NXL + NWL>(); else barrier_keep_vm<0>();
-#endif
+      if (!(LASNET_X1 & 2) || ch == 0 || ch + 1 == NCH)
+        barrier_keep_vm_n(conv1_keep_in_flight(ch, NCH, XD, NWL, NXL));
       __builtin_amdgcn_sched_barrier(0);
       l_bf16_cp xb = xs + (ch % K::NSTG) * K::STAGE_ELEMS;
 #pragma unroll
@@ -348,8 +378,9 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
           for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
         }
       }
-      // stage (ch+2)%3 was read during chunk ch-1, which every wave has left (barrier above)
-      if (ch + 2 < NCH && !(LASNET_X1 & 4)) issue_x(ch + 2);
+      // the stage of chunk ch+XD was last read during chunk ch-1, which every wave has left
+      // (barrier above)
+      if (ch + XD < NCH && !(LASNET_X1 & 4)) issue_x(ch + XD);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -371,12 +402,12 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
-        *reinterpret_cast<AS_LDS bf16x8*>(y1s + swz(row, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, row)) = join8(o[j], o[j + 1]);
+        *reinterpret_cast<AS_LDS bf16x8*>(y1s + swz(row, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, row, K::YMASK)) = join8(o[j], o[j + 1]);
     } else {
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
         const int c = lane_channel(chb, NBW, j, lg, 0);
-        *reinterpret_cast<AS_LDS bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row) + (c & 7)) = o[j];
+        *reinterpret_cast<AS_LDS bf16x4*>(y1s + swz(row, K::LDY, c >> 3, row, K::YMASK) + (c & 7)) = o[j];
       }
     }
   }
@@ -427,7 +458,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
   FragRow fr[RB];
   lookup(brow, 0);
 #pragma unroll
-  for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i]);
+  for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i], K::YMASK);
   // B fragments one k-step ahead of the MFMAs (bcur/bnxt); the row lookup of the next tap
   // happens while the last k-step of the current one is computed.
   bf16x8 bcur[RB], bnxt[RB];
@@ -445,7 +476,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
         if (msn == 0) {
           lookup(brow, (t + 1) / MS);
 #pragma unroll
-          for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i]);
+          for (int i = 0; i < RB; ++i) fr[i] = frag_row(brow[i], K::LDY, lg, brow[i], K::YMASK);
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i) bnxt[i] = frag_read(y1s, fr[i], msn);
@@ -477,12 +508,12 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
-        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, q)) = join8(o[j], o[j + 1]);
+        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, q, K::YMASK)) = join8(o[j], o[j + 1]);
     } else {
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
         const int c = lane_channel(chb, NBW, j, lg, 0);
-        *reinterpret_cast<AS_LDS bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q) + (c & 7)) = o[j];
+        *reinterpret_cast<AS_LDS bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q, K::YMASK) + (c & 7)) = o[j];
       }
     }
   }
@@ -506,7 +537,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
   for (int i = 0; i < RB; ++i) {
     const int bq = (wr + K::WR3 * i) * 16 + l16;
     pq[i] = pixq[bq];
-    fr[i] = frag_row(bq, K::LDY, lg, bq);
+    fr[i] = frag_row(bq, K::LDY, lg, bq, K::YMASK);
   }
   // this wave's weight stream is contiguous over (pass, k-step, tile)
   const rsrc_t wrs = make_rsrc(W3, (unsigned)(C * K::M * 2));
@@ -603,6 +634,7 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
   int* rowpix = reinterpret_cast<int*>(smem + K::OFF_ROWPIX);
   int* pixq = reinterpret_cast<int*>(smem + K::OFF_PIXQ);
   int* misc = reinterpret_cast<int*>(smem + K::OFF_MISC);      // [0] = number of unique rows
+  int* cellq = reinterpret_cast<int*>(smem + K::OFF_CELL);
   __bf16* y1s = reinterpret_cast<__bf16*>(smem + K::OFF_Y1);
   __bf16* xs = reinterpret_cast<__bf16*>(smem + K::OFF_XS);
   __bf16* y2s = xs;                                        // xs is dead once conv1 is done
@@ -638,6 +670,8 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
     // ---------------------------------------------------------------- phase 0
     int npb = min(te - e0, K::PPW);                        // patches in this batch
     int U;                                                 // unique window pixels = y1 rows
+    // the batch's cell ids: one round of global loads, every later step reads them from LDS
+    for (int i = tid; i < npb; i += K::NT) cellq[i] = idx ? idx[e0 + i] : e0 + i;
     for (;;) {
       for (int i = tid; i < K::HT; i += K::NT) hkey[i] = 0;
       if (tid == 0) misc[0] = 0;
@@ -645,7 +679,7 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
       // (a) every in-image window pixel claims a hash slot
       for (int t = tid; t < npb * WW; t += K::NT) {
         const int slot = t / WW, wp = t - slot * WW;
-        const int cell = idx ? idx[e0 + slot] : e0 + slot;
+        const int cell = cellq[slot];
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
         const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
@@ -682,7 +716,7 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
     // (c) row of every window position; pixel of every output row
     for (int t = tid; t < npb * WW; t += K::NT) {
       const int slot = t / WW, wp = t - slot * WW;
-      const int cell = idx ? idx[e0 + slot] : e0 + slot;
+      const int cell = cellq[slot];
       const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
       const int gy = rem / g.GW, gx = rem - gy * g.GW;
       const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
@@ -703,7 +737,7 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
       int pix = -1;
       if (q < nq) {
         const int slot = q / (S * S), r = q - slot * (S * S);
-        const int cell = idx ? idx[e0 + slot] : e0 + slot;
+        const int cell = cellq[slot];
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
         pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
@@ -788,10 +822,10 @@ using K_s1s7 = Cfg<256, 64, 7, 2, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;    
 // CU (<= 80 KB of LDS each), so that one workgroup's HBM-bound conv1 overlaps the other's
 // matrix work, instead of one 8-wave workgroup whose phases leave HBM or the matrix cores idle.
 using K_s2 = Cfg<512, 128, 4, 4, 112, 4, 64, 3, 1, 4, 1, 4, 12, 1, 4, 4, 4>;     // stage 2, S=4
-using K_s2s7 = Cfg<512, 128, 7, 1, 96, 4, 64, 3, 1, 4, 1, 4, 12, 1, 4, 4, 4>;    // stage 2, S=7 (dense tile)
-using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;       // stage 1, S=8
-using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // stage 1, S=4 (Table 1 block)
-using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 3, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // stage 1, S=7 (dense tile)
+using K_s2s7 = Cfg<512, 128, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 12, 1, 4, 4, 4>;    // stage 2, S=7 (dense tile)
+using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;       // stage 1, S=8: all of x in flight at once
+using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // stage 1, S=4 (Table 1 block)
+using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // stage 1, S=7 (dense tile)
 #endif
 
 #define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
