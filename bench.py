@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="stage3_b128",
-                    help="stage3_b128 (headline) | stage2_b128 | stage1_b64 | stage3_b1")
+                    help="stage3_b128 (headline) | stage2_b128 | stage1_b64 | stage4_b128 | stage3_b1")
     ap.add_argument("--ratio", type=float, default=None, help="activation ratio (default: the workload's)")
     ap.add_argument("--nbuf", type=int, default=6,
                     help="distinct x/out buffer pairs rotated over, so that steps see HBM-cold data")

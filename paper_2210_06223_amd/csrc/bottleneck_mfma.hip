@@ -114,7 +114,7 @@ struct Cfg {
   static constexpr int XD = NCH <= NSTG ? NCH : NSTG - 1;
   static_assert(NSTG >= 3 && XD >= 2, "x stream depth");
   static_assert(LDY % 64 == 0 && (LDY & (LDY - 1)) == 0, "y rows: power-of-two pitch, whole swizzle groups");
-  static_assert((9 * MS) % RD2 == 0 && RD2 % MS == 0 && MS % RD3 == 0, "weight rings");
+  static_assert((9 * MS) % RD2 == 0 && MS % RD3 == 0, "weight rings");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -471,7 +471,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
 #pragma unroll
     for (int tt = 0; tt < RD; ++tt) {
       const int t = t0 + tt;
-      const int msn = (tt + 1) % MS;                       // k-step inside the tap of step t+1 (RD is a multiple of MS)
+      const int msn = (t + 1) % MS;                        // k-step inside the tap of step t+1
       if (t + 1 < NSTEP) {
         if (msn == 0) {
           lookup(brow, (t + 1) / MS);
@@ -828,7 +828,11 @@ using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;    
 using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // stage 1, S=7 (dense tile)
 #endif
 
-#define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7)
+// Stage 4 (7x7 maps, pixel-level patches, 8.9 MB of weights): a workgroup is bound by streaming the
+// weights whatever it computes, so it takes up to 16 pixels and their 3x3 neighbourhoods.
+using K_s4 = Cfg<2048, 512, 1, 16, 96, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 4>;     // stage 4, S=1
+
+#define LASNET_FOR_EACH_MFMA_CFG(X) X(K_s3) X(K_s3s7) X(K_s2) X(K_s2s7) X(K_s1) X(K_s1s4) X(K_s1s7) X(K_s4)
 
 int device_cu_count() {
   static int cus = 0;                        // one kind of device per process

@@ -74,6 +74,8 @@ CONFIGS: Dict[str, BlockConfig] = {
     "stage1_b64": BlockConfig("stage1_b64", 64, 56, 56, 256, 64, 8, "bf16", 0.4, 2),
     # ResNet-101 stage 2, ratio sweep
     "stage2_b128": BlockConfig("stage2_b128", 128, 28, 28, 512, 128, 4, "bf16", 0.5, 3),
+    # ResNet-101 stage 4: 7x7 maps, pixel-level patches (S = 1)
+    "stage4_b128": BlockConfig("stage4_b128", 128, 7, 7, 2048, 512, 1, "bf16", 0.5, 4),
 }
 
 

@@ -35,6 +35,7 @@ MASKER_CASES = [
     _cfg("stage3_b128", N=5, name="stage3_n5"),
     _cfg("stage1_b64", N=2, name="stage1_n2"),
     _cfg("stage2_b128", N=3, name="stage2_n3"),
+    _cfg("stage4_b128", N=4, name="stage4_n4"),
     synth.BlockConfig("odd_c20_s3_f32", 2, 6, 9, 20, 12, 3, "f32", 0.5, 21),     # scalar-load path
     synth.BlockConfig("odd_c20_s1_bf16", 2, 5, 7, 20, 12, 1, "bf16", 0.3, 22),
     synth.BlockConfig("pixel_s1_manycells", 8, 32, 32, 8, 8, 1, "f32", 0.37, 23),  # P = 8192: 8 compaction rounds
@@ -101,6 +102,7 @@ MASKER_EX_CASES = [
     _cfg("stage3_b128", N=3, name="s3_ex"),        # matrix-core block kernel, hoisted masker path
     _cfg("stage2_b128", N=2, name="s2_ex"),
     _cfg("stage1_b64", N=1, name="s1_ex"),
+    _cfg("stage4_b128", N=3, name="s4_ex"),
     _cfg("tiny_f32"),                              # fp32, generic block kernel
     synth.BlockConfig("odd_c20_s3_f32_ex", 2, 6, 9, 20, 12, 3, "f32", 0.5, 26),     # scalar masker path
     synth.BlockConfig("odd_c24_s2_bf16_ex", 3, 4, 6, 24, 8, 2, "bf16", 0.4, 27),    # 16-byte pieces, ragged groups
@@ -203,6 +205,7 @@ MFMA_CASES = [
     (_cfg("stage1_b64", N=1, name="s1_S8"), 20),              # 49 cells
     (_cfg("stage1_b64", N=1, S=4, name="s1_S4"), 118),        # 196 cells (Table 1 block: S=4, r=0.6), ragged
     (_cfg("stage1_b64", N=1, S=7, name="s1_S7"), 31),         # 64 cells, ragged
+    (_cfg("stage4_b128", N=5, name="s4_S1"), 117),            # pixel-level patches: 245 cells, 8 tiles of <= 16
 ]
 
 
@@ -212,7 +215,7 @@ def test_mfma_kernel_matches_oracle(cfg, k):
     _run_case(cfg, k=k)
 
 
-@pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5],
+@pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5] + MFMA_CASES[7:8],
                          ids=lambda v: getattr(v, "name", str(v)))
 def test_mfma_extremes_and_flags(cfg, k):
     _run_case(cfg, k=0)                                        # ratio 0: identity, bit-exact
@@ -283,6 +286,7 @@ DENSE_CASES = [
     _cfg("stage3_b128", N=2, name="dense_s3"),
     _cfg("stage2_b128", N=1, name="dense_s2"),
     _cfg("stage1_b64", N=1, name="dense_s1"),
+    _cfg("stage4_b128", N=2, name="dense_s4"),
     synth.BlockConfig("dense_gen_bf16", 2, 6, 4, 24, 8, 2, "bf16", 1.0, 41),
 ]
 
