@@ -11,7 +11,7 @@
 //            ONE row, pixels outside the image get none -- the overlapping neighbour area
 //            of Sec. 3.4 is loaded and convolved once per workgroup, not once per patch
 //   phase 1  conv1 over the U unique rows: x rows stream through LDS in KC-channel chunks
-//            (double buffered), y1 = ReLU(W1 x + b1) -> LDS
+//            (2-4 chunks requested ahead), y1 = ReLU(W1 x + b1) -> LDS
 //   phase 2  conv2: implicit GEMM over the 9 taps, y1 rows looked up per window position
 //            (an all-zero row stands for "outside the image") -> y2 in LDS
 //   phase 3  conv3 + b3 + residual x, rounded once, stored at the patch's own pixels
@@ -20,8 +20,9 @@
 // v_mfma_f32_16x16x32_bf16.  The weight fragment (A operand) is read straight from global
 // memory / L2, from a buffer that pack_weights_kernel has laid out fragment by fragment in
 // the order the waves consume them; the activation fragment (B operand) comes from LDS.
-// In the result a lane holds 4 consecutive rows = channels; the rows of the NB tiles of a
-// pass are interleaved so that a lane ends up with 4*NB consecutive channels of one pixel.
+// In the result a lane holds 4 consecutive rows = channels; which channel sits in which row
+// of which tile is chosen (lane_channel) so that a lane's results are runs of 8 consecutive
+// channels and four lanes cover 64 contiguous bytes of a pixel.
 // Waves are arranged WR x WC (pixel-blocks x channel-blocks) per phase.
 #include "common.hpp"
 
@@ -30,12 +31,6 @@
 namespace lasnet {
 namespace {
 
-// Timing experiments on conv1 (debug builds only; results are wrong when set): bit 0 no LDS
-// reads after the first chunk, 1 no barriers between chunks, 2 no x loads after the first two
-// chunks, 3 no weight loads after the first two chunks, 4 no MFMAs after the first chunk.
-#ifndef LASNET_X1
-#define LASNET_X1 0
-#endif
 #ifdef LASNET_PHASE_CLOCKS
 __device__ long long g_phase_clk[6 * 2048];
 #define PHASE_MARK(i)                                                            \
@@ -355,32 +350,31 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const int ch = ch2 + cc;
-      if (!(LASNET_X1 & 2) || ch == 0 || ch + 1 == NCH)
-        barrier_keep_vm_n(conv1_keep_in_flight(ch, NCH, XD, NWL, NXL));
+      barrier_keep_vm_n(conv1_keep_in_flight(ch, NCH, XD, NWL, NXL));
       __builtin_amdgcn_sched_barrier(0);
       l_bf16_cp xb = xs + (ch % K::NSTG) * K::STAGE_ELEMS;
 #pragma unroll
-      for (int i = 0; i < RB; ++i) if (!(LASNET_X1 & 1) || ch == 0) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][0]);
+      for (int i = 0; i < RB; ++i) bcur[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][0]);
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        if (s + 1 < KS && (!(LASNET_X1 & 1) || ch == 0)) {
+        if (s + 1 < KS) {
 #pragma unroll
           for (int i = 0; i < RB; ++i) bnxt[i] = *reinterpret_cast<const AS_LDS bf16x8*>(xb + boff[i][s + 1]);
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i)
 #pragma unroll
-          for (int j = 0; j < NBW; ++j) if (!(LASNET_X1 & 16) || ch == 0) acc[i][j] = mfma16(w[cc * KS + s][j], bcur[i], acc[i][j]);
-        if (ch + 2 < NCH && !(LASNET_X1 & 8)) wload(cc * KS + s, (ch + 2) * KS + s);
+          for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[cc * KS + s][j], bcur[i], acc[i][j]);
+        if (ch + 2 < NCH) wload(cc * KS + s, (ch + 2) * KS + s);
         __builtin_amdgcn_sched_barrier(0);
-        if (s + 1 < KS && (!(LASNET_X1 & 1) || ch == 0)) {
+        if (s + 1 < KS) {
 #pragma unroll
           for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
         }
       }
       // the stage of chunk ch+XD was last read during chunk ch-1, which every wave has left
       // (barrier above)
-      if (ch + XD < NCH && !(LASNET_X1 & 4)) issue_x(ch + XD);
+      if (ch + XD < NCH) issue_x(ch + XD);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -551,11 +545,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
   // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
-#ifdef LASNET_C3_NOUNROLL
-#pragma nounroll
-#else
 #pragma unroll
-#endif
   for (int pass = 0; pass < NPASS; ++pass) {
     const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
     // residual and bias are requested before the GEMM so that their latency hides behind it
@@ -811,13 +801,6 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const __bf16* __restr
 //             C     M   S PPW R1MAX NW KC NSTG conv1  conv2 RD2  conv3 NB3 RD3
 using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // ResNet-101 stage 3, S=2
 using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 3, 1, 8, 1, 8, 8, 1, 8, 4, 4>;    // stage 3, S=7 (also the dense tile)
-#ifdef LASNET_BIGWG
-using K_s2 = Cfg<512, 128, 4, 8, 224, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;     // stage 2, S=4
-using K_s2s7 = Cfg<512, 128, 7, 2, 192, 8, 64, 3, 2, 4, 1, 8, 12, 1, 8, 2, 4>;   // stage 2, S=7 (dense tile)
-using K_s1 = Cfg<256, 64, 8, 2, 224, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;       // stage 1, S=8
-using K_s1s4 = Cfg<256, 64, 4, 6, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=4 (Table 1 block)
-using K_s1s7 = Cfg<256, 64, 7, 2, 192, 8, 64, 3, 2, 4, 2, 4, 6, 1, 8, 2, 2>;     // stage 1, S=7 (dense tile)
-#else
 // Stages 1 and 2 have small weights (0.14 / 0.56 MB) and large maps: two 4-wave workgroups per
 // CU (<= 80 KB of LDS each), so that one workgroup's HBM-bound conv1 overlaps the other's
 // matrix work, instead of one 8-wave workgroup whose phases leave HBM or the matrix cores idle.
@@ -826,7 +809,6 @@ using K_s2s7 = Cfg<512, 128, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 12, 1, 4, 4, 4>;   
 using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;       // stage 1, S=8: all of x in flight at once
 using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // stage 1, S=4 (Table 1 block)
 using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // stage 1, S=7 (dense tile)
-#endif
 
 // Stage 4 (7x7 maps, pixel-level patches, 8.9 MB of weights): a workgroup is bound by streaming the
 // weights whatever it computes, so it takes up to 16 pixels and their 3x3 neighbourhoods.
