@@ -340,3 +340,29 @@ def test_headline_workload_full_size_matches_oracle():
     device-resident count, every output element against the oracle."""
     cfg = synth.CONFIGS["stage3_b128"]
     _run_case(cfg, k=cfg.P // 2)
+
+
+@pytest.mark.parametrize("name", ["stage3_b128", "stage2_b128", "stage1_b64", "stage4_b128"])
+def test_full_size_workloads_as_the_benchmark_launches_them(name):
+    """The step bench.py times, at full size: lasnet_masker_ex (identity pass-through into out) then
+    the block with LASNET_SKIP_IDENTITY through the prepacked-weights entry; every element of a
+    poisoned out against the oracle, masks and index list bit-exact."""
+    cfg = synth.CONFIGS[name]
+    _say("full size", cfg)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    k = int(round(cfg.r * cfg.P))
+    bm = U.calibrate(inp, k)
+    mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+    out = torch.full_like(d["x"], 768.0)
+    mask, idx, count = B.lasnet_masker_ex(d["x"], d["Wm"], bm, cfg.S, 0.0, pass_out=out)
+    packed = B.lasnet_pack_weights(cfg.S, d["W1"], d["W2"], d["W3"])
+    B.lasnet_sparse_bottleneck_packed(d["x"], idx, count, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
+                                      out=out, flags=B.LASNET_SKIP_IDENTITY)
+    torch.cuda.synchronize()
+    assert int(count.item()) == count_o == k
+    assert np.array_equal(mask.cpu().numpy(), mask_o)
+    assert np.array_equal(idx.cpu().numpy()[:k], idx_o)
+    ref = O.sparse_bottleneck(inp.f64["x"], mask_o, cfg.S, *_oracle_w(inp))
+    up = np.broadcast_to(O.upsample_mask(mask_o, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(out, ref, d["x"], up, cfg.dtype, cfg.name)
