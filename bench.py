@@ -48,6 +48,9 @@ def parse_args():
                     help="distinct x/out buffer pairs rotated over, so that steps see HBM-cold data")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-torch-dense", action="store_true")
+    ap.add_argument("--granularity", action="store_true",
+                    help="also time the path at every patch size S that divides H and has a matrix-core kernel "
+                         "(the latency-ratio-against-S curve of Sec. 4.2 on this GPU)")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the block alone over r in {0.1,.25,.5,.75,1} (index lists fed directly)")
     return ap.parse_args()
@@ -247,6 +250,35 @@ def main():
                               "latency_ratio_vs_dense": t_skip / dense_loop})
         sweep_note = {"dense_ms": dense_loop, "timing": "mean over 50 back-to-back launches between two events"}
 
+    gran = None
+    if args.granularity and packed is not None:
+        gran = []
+        dense_ms = dense_packed_ms
+        for S_g in range(1, cfg.H + 1):
+            if cfg.H % S_g or cfg.W % S_g or B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, S_g) != 1:
+                continue
+            Pg = cfg.N * (cfg.H // S_g) * (cfg.W // S_g)
+            lg0 = B.lasnet_masker_logits(d["x"], d["Wm"], 0.0, S_g).cpu().numpy()
+            bm_g, _ = synth.bias_for_count(lg0, int(round(cfg.r * Pg)))
+            mask_g = torch.empty((cfg.N, cfg.H // S_g, cfg.W // S_g), dtype=torch.uint8, device=dev)
+            idx_g = torch.empty((Pg,), dtype=torch.int32, device=dev)
+            cnt_g = torch.zeros((1,), dtype=torch.int32, device=dev)
+            packed_g = B.lasnet_pack_weights(S_g, d["W1"], d["W2"], d["W3"])
+
+            def step_g(i):
+                B.lasnet_masker_ex(xs[i % nbuf], d["Wm"], bm_g, S_g, 0.0, mask=mask_g, idx=idx_g, count=cnt_g,
+                                   pass_out=outs[i % nbuf])
+                B.lasnet_sparse_bottleneck_packed(xs[i % nbuf], idx_g, cnt_g, S_g, cfg.M, packed_g, d["b1"], d["b2"],
+                                                  d["b3"], out=outs[i % nbuf], flags=B.LASNET_SKIP_IDENTITY)
+
+            t_step = timed_loop(step_g, 50)
+            t_block = timed_loop(lambda i: B.lasnet_sparse_bottleneck_packed(
+                xs[i % nbuf], idx_g, cnt_g, S_g, cfg.M, packed_g, d["b1"], d["b2"], d["b3"], out=outs[i % nbuf],
+                flags=B.LASNET_SKIP_IDENTITY), 50)
+            gran.append({"S": S_g, "cells": Pg, "active": int(cnt_g.item()), "step_ms": t_step, "block_ms": t_block,
+                         "latency_ratio_vs_dense_block": t_block / dense_ms,
+                         "latency_ratio_step_vs_dense_block": t_step / dense_ms})
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, inp, bm)
@@ -289,6 +321,10 @@ def main():
                      "avg_launch_ms_single_event_pairs": fused_t["mean_ms"], "launches_timed": reps},
         "cpu_baseline": cpu,
     }
+    if gran is not None:
+        result["granularity_sweep"] = gran
+        result["granularity_sweep_note"] = ("r = %.2f at every S (masker bias recalibrated per S); prepacked weights; "
+                                            "dense block %.4f ms; mean over 50 back-to-back launches" % (cfg.r, dense_packed_ms))
     if sweep is not None:
         result["ratio_sweep"] = sweep
         result["ratio_sweep_note"] = sweep_note

@@ -11,7 +11,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblasnet.so")
-SOURCES = ["api.hip", "masker.hip", "bottleneck_generic.hip", "bottleneck_mfma.hip"]
+SOURCES = ["mfma_stage3.hip", "mfma_stage2.hip", "mfma_stage1.hip", "mfma_stage4.hip",   # slowest first
+           "api.hip", "masker.hip", "bottleneck_generic.hip", "bottleneck_mfma.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -44,7 +45,7 @@ def build_library(verbose: bool = True, extra_flags=(), out: str = LIB, build_di
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES), os.cpu_count() or 1)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     tmp = out + ".tmp"
     r = subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],

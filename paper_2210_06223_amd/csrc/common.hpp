@@ -39,6 +39,17 @@ hipError_t launch_generic(int dtype, const Geom& g, const void* x, const int32_t
                           const int32_t* count, const BlockWeights& w, void* out, bool post_relu,
                           hipStream_t st);
 
+// One matrix-core instantiation: its shape and its two launchers.
+struct MfmaVariant {
+  int C, M, S;
+  size_t packed_bytes;
+  hipError_t (*pack)(const void* W1, const void* W2, const void* W3, void* packed, hipStream_t st);
+  hipError_t (*launch)(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
+                       const void* packed, const float* b1, const float* b2, const float* b3,
+                       void* out, bool post_relu, hipStream_t st);
+};
+int device_cu_count();
+
 // Matrix-core kernel: only for the (C, M, S) it was instantiated for.  It reads the three
 // weight tensors from one buffer of mfma_packed_bytes() that launch_pack() fills.
 bool mfma_supported(int C, int M, int S);

@@ -206,6 +206,12 @@ MFMA_CASES = [
     (_cfg("stage1_b64", N=1, S=4, name="s1_S4"), 118),        # 196 cells (Table 1 block: S=4, r=0.6), ragged
     (_cfg("stage1_b64", N=1, S=7, name="s1_S7"), 31),         # 64 cells, ragged
     (_cfg("stage4_b128", N=5, name="s4_S1"), 117),            # pixel-level patches: 245 cells, 8 tiles of <= 16
+    # other granularities of the same stages (Sec. 3.2: S ranges over the divisors of H)
+    (_cfg("stage3_b128", N=2, S=1, name="s3_S1"), 201),       # 392 pixel-level cells, tiles of <= 64
+    (_cfg("stage2_b128", N=1, S=2, name="s2_S2"), 95),        # 196 cells
+    (_cfg("stage2_b128", N=1, S=1, name="s2_S1"), 391),       # 784 cells, tiles of <= 24
+    (_cfg("stage1_b64", N=1, S=2, name="s1_S2"), 401),        # 784 cells
+    (_cfg("stage1_b64", N=1, S=1, name="s1_S1"), 1570),       # 3136 cells, tiles of <= 16
 ]
 
 
@@ -215,7 +221,7 @@ def test_mfma_kernel_matches_oracle(cfg, k):
     _run_case(cfg, k=k)
 
 
-@pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5] + MFMA_CASES[7:8],
+@pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5] + MFMA_CASES[7:9] + MFMA_CASES[10:11],
                          ids=lambda v: getattr(v, "name", str(v)))
 def test_mfma_extremes_and_flags(cfg, k):
     _run_case(cfg, k=0)                                        # ratio 0: identity, bit-exact
