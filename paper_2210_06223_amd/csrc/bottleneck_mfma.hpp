@@ -113,6 +113,7 @@ struct Cfg {
   static_assert(LDY % 64 == 0 && (LDY & (LDY - 1)) == 0, "y rows: power-of-two pitch, whole swizzle groups");
   static_assert((9 * MS) % RD2 == 0 && MS % RD3 == 0, "weight rings");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  static_assert(NW * 2048 <= R1MAX * LDY * 2, "conv3's per-wave transpose areas sit in the y1 rows below the zero row");
 };
 
 // Pointers into global memory and LDS carry explicit address spaces: through generic pointers
@@ -518,7 +519,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
 // ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
 template <class K, int NB2>
 __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p b3, l_i32_cp pixq,
-                                                      l_bf16_cp y2s, AS_GLOBAL __bf16* out,
+                                                      l_bf16_cp y2s, l_bf16_p tscratch, AS_GLOBAL __bf16* out,
                                                       int post_relu, int tid, int wave) {
   constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
   constexpr int NPASS = K::NBT3 / NB, NSTEP = NPASS * MS;
@@ -589,23 +590,46 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
     }
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
-      if (pq[i] >= 0) {
-        const size_t off = (size_t)pq[i] * C;
+      bf16x8 o[NB / 2];
 #pragma unroll
-        for (int j = 0; j < NB; j += 2) {
-          bf16x8 o;
+      for (int j = 0; j < NB; j += 2) {
 #pragma unroll
-          for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              float r = (float)xres[i][j / 2][h * 4 + v] + (acc[i][j + h][v] + bias[j + h][v]);
-              if (post_relu) r = fmaxf(r, 0.f);
-              o[h * 4 + v] = (__bf16)r;
-            }
+          for (int v = 0; v < 4; ++v) {
+            float r = (float)xres[i][j / 2][h * 4 + v] + (acc[i][j + h][v] + bias[j + h][v]);
+            if (post_relu) r = fmaxf(r, 0.f);
+            o[j / 2][h * 4 + v] = (__bf16)r;
           }
-          // streaming store: out is not read again here, and lines left dirty in L2 would all be
-          // written back in one burst when the kernel ends
-          __builtin_nontemporal_store(o, reinterpret_cast<AS_GLOBAL bf16x8*>(out + off + lane_channel(chb, NB, j, lg, 0)));
+        }
+      }
+      // Streaming stores (out is not read again here; lines left dirty in L2 would all be written
+      // back in one burst when the kernel ends).
+      if constexpr (NB == 4) {
+        // A pass gives a lane 2 x 16 bytes of its pixel and the four lane groups one 128-byte line of
+        // it, but a store instruction in that layout scatters 16-byte pieces over 16 lines.  The
+        // wave transposes the 16 x 128 bytes through 2 KiB of LDS of its own (inside the y1 region,
+        // which is dead during conv3; rows swizzled like every other LDS row), so that each store
+        // instruction writes 8 whole lines, 8 consecutive lanes per line.
+        AS_LDS char* tr = reinterpret_cast<AS_LDS char*>(tscratch) + wave * 2048;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          *reinterpret_cast<AS_LDS bf16x8*>(tr + l16 * 128 + (((4 * t + lg) ^ (l16 & 7)) << 4)) = o[t];
+        const int c8 = lane & 7;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int p = half * 8 + (lane >> 3);                    // pixel (row of the block) this lane stores for
+          const bf16x8 v = *reinterpret_cast<const AS_LDS bf16x8*>(tr + p * 128 + ((c8 ^ (p & 7)) << 4));
+          const int pix = pixq[(wr + K::WR3 * i) * 16 + p];
+          if (pix >= 0)
+            __builtin_nontemporal_store(v, reinterpret_cast<AS_GLOBAL bf16x8*>(out + (size_t)pix * C + chb + c8 * 8));
+        }
+      } else {
+        if (pq[i] >= 0) {
+#pragma unroll
+          for (int j = 0; j < NB; j += 2)
+            __builtin_nontemporal_store(o[j / 2], reinterpret_cast<AS_GLOBAL bf16x8*>(
+                                                      out + (size_t)pq[i] * C + lane_channel(chb, NB, j, lg, 0)));
         }
       }
     }
@@ -756,7 +780,7 @@ __global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves 
     PHASE_MARK(3);
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (g_f32_p)b3, (l_i32_cp)pixq,
-                                                 (l_bf16_cp)y2s, (AS_GLOBAL __bf16*)out, post_relu, tid, wave);
+                                                 (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, tid, wave);
     });
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch
