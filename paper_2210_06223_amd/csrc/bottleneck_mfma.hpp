@@ -113,6 +113,9 @@ struct Cfg {
   static_assert(LDY % 64 == 0 && (LDY & (LDY - 1)) == 0, "y rows: power-of-two pitch, whole swizzle groups");
   static_assert((9 * MS) % RD2 == 0 && MS % RD3 == 0, "weight rings");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  // Waves a SIMD holds when the CU is full of these workgroups: the register budget per wave
+  // is 512 / that (a 4-wave workgroup alone on its CU may use the accumulation registers too).
+  static constexpr int WAVES_PER_SIMD = cmax(1, ((160 * 1024) / LDS_BYTES) * NW / 4);
   static_assert(NW * 2048 <= R1MAX * LDY * 2, "conv3's per-wave transpose areas sit in the y1 rows below the zero row");
 };
 
@@ -637,7 +640,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 }
 
 template <class K>
-__global__ __launch_bounds__(K::NT, 2) void fused_bneck_kernel(   // >= 2 waves per SIMD: at most 256 registers
+__global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     Geom g, int tile_slots, const __bf16* __restrict__ x, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ count, const __bf16* __restrict__ W1,
     const float* __restrict__ b1, const __bf16* __restrict__ W2, const float* __restrict__ b2,

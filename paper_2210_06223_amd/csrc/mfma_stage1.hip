@@ -6,11 +6,7 @@ namespace {
 //             C     M   S PPW R1MAX NW KC NSTG conv1  conv2 RD2  conv3 NB3 RD3
 // Two 4-wave workgroups per CU (see stage 2); x is only 4 chunks of 64 channels deep, so all of a
 // batch's x is requested at once (NSTG = 4).
-#ifdef LASNET_TUNE_S1
-using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 4, LASNET_TUNE_S1>;
-#else
 using K_s1 = Cfg<256, 64, 8, 1, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;       // S=8
-#endif
 using K_s1s4 = Cfg<256, 64, 4, 4, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // S=4 (the block of Table 1)
 using K_s1s7 = Cfg<256, 64, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;      // S=7 (dense tile)
 using K_s1s2 = Cfg<256, 64, 2, 8, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;     // S=2

@@ -7,11 +7,7 @@ namespace {
 // Stages 1 and 2 have small weights (0.14 / 0.56 MB) and large maps: two 4-wave workgroups per
 // CU (<= 80 KB of LDS each), so that one workgroup's HBM-bound conv1 overlaps the other's
 // matrix work, instead of one 8-wave workgroup whose phases leave HBM or the matrix cores idle.
-#ifdef LASNET_TUNE_S2
-using K_s2 = Cfg<512, 128, 4, 4, 112, 4, 64, 3, LASNET_TUNE_S2>;
-#else
 using K_s2 = Cfg<512, 128, 4, 4, 112, 4, 64, 3, 1, 4, 1, 4, 4, 1, 4, 4, 2>;      // S=4
-#endif
 using K_s2s7 = Cfg<512, 128, 7, 1, 96, 4, 64, 4, 1, 4, 1, 4, 4, 1, 4, 4, 2>;     // S=7 (dense tile)
 using K_s2s2 = Cfg<512, 128, 2, 8, 112, 4, 64, 3, 1, 4, 1, 4, 4, 1, 4, 4, 2>;    // S=2
 using K_s2s1 = Cfg<512, 128, 1, 24, 112, 4, 64, 3, 1, 4, 1, 4, 4, 1, 4, 4, 2>;   // S=1 (pixel level)

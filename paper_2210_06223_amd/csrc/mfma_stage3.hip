@@ -8,11 +8,7 @@ namespace {
 // the weights stream through a CU once per batch.
 // (weight rings of 4 and 2 steps: deeper ones cost registers, and spills inside the k-loops
 // cost more than the extra latency cover is worth -- measured 46 us against 49)
-#ifdef LASNET_TUNE_S3
-using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, LASNET_TUNE_S3>;
-#else
 using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // S=2
-#endif
 using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // S=7 (also the dense tile)
 using K_s3s1 = Cfg<1024, 256, 1, 64, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;  // S=1 (pixel level)
 }  // namespace
