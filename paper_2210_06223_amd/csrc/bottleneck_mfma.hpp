@@ -89,7 +89,8 @@ struct Cfg {
   static constexpr int OFF_PIXQ = OFF_ROWPIX + R1MAX * 4;       // int  [R2P]
   static constexpr int OFF_MISC = OFF_PIXQ + R2P * 4;           // int  [4]
   static constexpr int OFF_CELL = OFF_MISC + 16;                // int  [PPW]    cell ids of the batch
-  static constexpr int OFF_Y1 = (OFF_CELL + PPW * 4 + 15) / 16 * 16;
+  static constexpr int OFF_BIAS = (OFF_CELL + PPW * 4 + 15) / 16 * 16;   // float[M | M | C]: b1, b2, b3
+  static constexpr int OFF_Y1 = OFF_BIAS + (2 * M + C) * 4;
   static constexpr int Y1_BYTES = (R1MAX + 1) * LDY * 2;
   static constexpr int OFF_XS = OFF_Y1 + Y1_BYTES;
   static constexpr int STAGE_ELEMS = R1MAX * LDX;
@@ -137,6 +138,7 @@ typedef AS_LDS __bf16* l_bf16_p;
 typedef const AS_LDS __bf16* l_bf16_cp;
 typedef const AS_LDS int* l_i32_cp;
 typedef const AS_LDS short* l_i16_cp;
+typedef const AS_LDS float* l_f32_cp;
 
 // Element offset of 16-byte chunk `chunk` in an LDS row of pitch `ld` elements whose chunks
 // are XOR-swizzled with `key` (low 4 bits of the chunk index at most).
@@ -268,7 +270,7 @@ __device__ __forceinline__ bf16x8 buf_load16(rsrc_t r, int lane_bytes, int unifo
 // the lane picks the global chunk whose swizzled position it writes), three stages deep;
 // the weights of the next two chunks are always in flight in registers.
 template <class K, int NB1>
-__device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p b1, l_i32_cp rowpix,
+__device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_cp b1s, l_i32_cp rowpix,
                                                       l_bf16_p xs, l_bf16_p y1s, int tid, int wave) {
   constexpr int C = K::C, M = K::M, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
   constexpr int RB = cdiv(NB1, K::WR1);                   // row blocks of this wave (last may be padding)
@@ -279,11 +281,16 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
   wave = uni(wave);
   const int wr = wave / K::WC1, wc = wave % K::WC1;
 
+  // the accumulators start at the bias (read from LDS: the first MFMA of each takes it as its
+  // C operand), so the epilogue has no add
+  const int chb = wc * NBW * 16;
   floatx4 acc[RB][NBW];
 #pragma unroll
-  for (int i = 0; i < RB; ++i)
+  for (int j = 0; j < NBW; ++j) {
+    const floatx4 bias = *reinterpret_cast<const AS_LDS floatx4*>(b1s + lane_channel(chb, NBW, j, lg, 0));
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < RB; ++i) acc[i][j] = bias;
+  }
 
   // x stream: group u of this wave = rows grp*8 .. grp*8+7
   g_bf16_p xsrc[NXL];
@@ -384,13 +391,7 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  // epilogue: + b1, ReLU, round to bf16; 8 channels (one 16-byte chunk) per LDS store where NBW allows
-  const int chb = wc * NBW * 16;
-  float bias[NBW][4];
-#pragma unroll
-  for (int j = 0; j < NBW; ++j)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) bias[j][v] = b1[lane_channel(chb, NBW, j, lg, v)];
+  // epilogue: ReLU, round to bf16; 8 channels (one 16-byte chunk) per LDS store where NBW allows
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int row = (wr + K::WR1 * i) * 16 + l16;
@@ -398,7 +399,7 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v] + bias[j][v], 0.f);
+      for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v], 0.f);
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
@@ -415,7 +416,7 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, g_f32_p
 
 // ---- phase 2: conv3x3 as an implicit GEMM over the 9 taps, y1 rows from LDS ---------------
 template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_cp winrow, l_bf16_cp y1s,
+__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16_cp winrow, l_bf16_cp y1s,
                                                       l_bf16_p y2s, int nq, int tid, int wave) {
   constexpr int M = K::M, S = K::S, T = K::T, WW = K::WW;
   constexpr int NBW = K::NBW2, MS = K::MS, RD = K::RD2, NSTEP = 9 * MS;
@@ -424,11 +425,14 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
   const int lane16 = lane * 16;
   wave = uni(wave);
   const int wr = wave / K::WC2, wc = wave % K::WC2;
-  floatx4 acc[RB][NBW];
+  const int chb = wc * NBW * 16;
+  floatx4 acc[RB][NBW];                                    // start at the bias, like conv1's
 #pragma unroll
-  for (int i = 0; i < RB; ++i)
+  for (int j = 0; j < NBW; ++j) {
+    const floatx4 bias = *reinterpret_cast<const AS_LDS floatx4*>(b2s + lane_channel(chb, NBW, j, lg, 0));
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < RB; ++i) acc[i][j] = bias;
+  }
   int wpos[RB];                                            // window position of tap (0,0)
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
@@ -491,12 +495,6 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
       for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
     }
   }
-  const int chb = wc * NBW * 16;
-  float bias[NBW][4];
-#pragma unroll
-  for (int j = 0; j < NBW; ++j)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) bias[j][v] = b2[lane_channel(chb, NBW, j, lg, v)];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int q = (wr + K::WR2 * i) * 16 + l16;
@@ -504,7 +502,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v] + bias[j][v], 0.f);
+      for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v], 0.f);
     if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
@@ -521,7 +519,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, g_f32_p b2, l_i16_c
 
 // ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
 template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p b3, l_i32_cp pixq,
+__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_cp b3s, l_i32_cp pixq,
                                                       l_bf16_cp y2s, l_bf16_p tscratch, AS_GLOBAL __bf16* out,
                                                       int post_relu, int tid, int wave) {
   constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
@@ -531,6 +529,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
   const int lane16 = lane * 16;
   wave = uni(wave);
   const int wr = wave / K::WC3, wc = wave % K::WC3;
+  const float floor_ = post_relu ? 0.f : -__builtin_inff();   // ReLU after the add, or nothing
   int pq[RB];
   FragRow fr[RB];
 #pragma unroll
@@ -554,21 +553,20 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
     const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
-    // residual and bias are requested before the GEMM so that their latency hides behind it
+    // the residual is requested before the GEMM so that its latency hides behind it
     bf16x8 xres[RB][NB / 2];
 #pragma unroll
     for (int i = 0; i < RB; ++i)
 #pragma unroll
       for (int j = 0; j < NB / 2; ++j)   // rows past the last pixel read pixel 0 (never stored)
         xres[i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq[i], 0) * C + lane_channel(chb, NB, 2 * j, lg, 0));
-    floatx4 bias[NB];
+    floatx4 acc[RB][NB];                                   // start at the bias
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bias[j] = *reinterpret_cast<const AS_GLOBAL floatx4*>(b3 + lane_channel(chb, NB, j, lg, 0));
-    floatx4 acc[RB][NB];
+    for (int j = 0; j < NB; ++j) {
+      const floatx4 bias = *reinterpret_cast<const AS_LDS floatx4*>(b3s + lane_channel(chb, NB, j, lg, 0));
 #pragma unroll
-    for (int i = 0; i < RB; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < RB; ++i) acc[i][j] = bias;
+    }
     bf16x8 bcur[RB], bnxt[RB];
 #pragma unroll
     for (int i = 0; i < RB; ++i) bcur[i] = frag_read(y2s, fr[i], 0);
@@ -600,9 +598,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, g_f32_p
         for (int h = 0; h < 2; ++h) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            float r = (float)xres[i][j / 2][h * 4 + v] + (acc[i][j + h][v] + bias[j + h][v]);
-            if (post_relu) r = fmaxf(r, 0.f);
-            o[j / 2][h * 4 + v] = (__bf16)r;
+            o[j / 2][h * 4 + v] = (__bf16)fmaxf((float)xres[i][j / 2][h * 4 + v] + acc[i][j + h][v], floor_);
           }
         }
       }
@@ -654,6 +650,9 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
   int* pixq = reinterpret_cast<int*>(smem + K::OFF_PIXQ);
   int* misc = reinterpret_cast<int*>(smem + K::OFF_MISC);      // [0] = number of unique rows
   int* cellq = reinterpret_cast<int*>(smem + K::OFF_CELL);
+  float* b1s = reinterpret_cast<float*>(smem + K::OFF_BIAS);
+  float* b2s = b1s + K::M;
+  float* b3s = b2s + K::M;
   __bf16* y1s = reinterpret_cast<__bf16*>(smem + K::OFF_Y1);
   __bf16* xs = reinterpret_cast<__bf16*>(smem + K::OFF_XS);
   __bf16* y2s = xs;                                        // xs is dead once conv1 is done
@@ -681,9 +680,11 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
   const int te = (int)(((long long)(tile + 1) * nact) / nt);
   PHASE_MARK(0);
 
-  // the all-zero y1 row
+  // the all-zero y1 row; the biases (phase 0's barriers come before their first use)
   for (int i = tid; i < K::LDY / 8; i += K::NT)
     *reinterpret_cast<uint4*>(y1s + K::ZROW * K::LDY + i * 8) = uint4{0, 0, 0, 0};
+  for (int i = tid; i < K::M; i += K::NT) { b1s[i] = b1[i]; b2s[i] = b2[i]; }
+  for (int i = tid; i < K::C; i += K::NT) b3s[i] = b3[i];
 
   for (int e0 = tb; e0 < te;) {
     // ---------------------------------------------------------------- phase 0
@@ -769,20 +770,20 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     // Row blocks are dealt to the wave rows round-robin (wave row wr takes blocks wr, wr+WR,
     // ...); the count is rounded up to a multiple of WR, the extra blocks compute unused rows.
     dispatch_count<1, K::R1B / K::WR1>((nblk1 + K::WR1 - 1) / K::WR1, [&](auto nb) {
-      conv1_phase<K, decltype(nb)::value * K::WR1>((g_bf16_p)x, (g_bf16_p)W1, (g_f32_p)b1, (l_i32_cp)rowpix,
+      conv1_phase<K, decltype(nb)::value * K::WR1>((g_bf16_p)x, (g_bf16_p)W1, (l_f32_cp)b1s, (l_i32_cp)rowpix,
                                                    (l_bf16_p)xs, (l_bf16_p)y1s, tid, wave);
     });
     __syncthreads();
     PHASE_MARK(2);
     constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
-      conv2_phase<K, decltype(nb)::value * WR23>((g_bf16_p)W2, (g_f32_p)b2, (l_i16_cp)winrow, (l_bf16_cp)y1s,
+      conv2_phase<K, decltype(nb)::value * WR23>((g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s,
                                                  (l_bf16_p)y2s, nq, tid, wave);
     });
     __syncthreads();
     PHASE_MARK(3);
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
-      conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (g_f32_p)b3, (l_i32_cp)pixq,
+      conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq,
                                                  (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, tid, wave);
     });
     e0 += npb;

@@ -217,8 +217,10 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
       FragRow fr[K::RB1];
 #pragma unroll
       for (int i = 0; i < K::RB1; ++i) {
+        // the accumulators start at the bias: the first MFMA takes it as its C operand
 #pragma unroll
-        for (int tt = 0; tt < K::MT; ++tt) acc[i][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < K::MT; ++tt)
+          acc[i][tt] = *reinterpret_cast<AS_LDS const floatx4*>(b1s + (wc * K::MT + tt) * 16 + lg * 4);
         // a wave row's last block may not exist (R1B not a multiple of WR): it recomputes the
         // last real one, and its result is dropped
         const int row = min(wr + K::WR * i, K::R1B - 1) * 16 + l16;
@@ -254,10 +256,9 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
 #pragma unroll
           for (int tt = 0; tt < K::MT; ++tt) {
             const int ch = (wc * K::MT + tt) * 16 + lg * 4;   // this lane's 4 channels of the tile
-            const floatx4 bias = *reinterpret_cast<AS_LDS const floatx4*>(b1s + ch);
             bf16x4 o;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = (__bf16)(in ? fmaxf(acc[i][tt][v] + bias[v], 0.f) : 0.f);
+            for (int v = 0; v < 4; ++v) o[v] = (__bf16)(in ? fmaxf(acc[i][tt][v], 0.f) : 0.f);
             *reinterpret_cast<AS_LDS bf16x4*>(y1s + row * K::YROW + (((ch >> 3) ^ y1_key(row)) << 4) + (ch & 7) * 2) = o;
           }
         }
@@ -274,7 +275,8 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
 #pragma unroll
       for (int i = 0; i < K::RB2; ++i) {
 #pragma unroll
-        for (int tt = 0; tt < K::MT; ++tt) acc[i][tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < K::MT; ++tt)
+          acc[i][tt] = *reinterpret_cast<AS_LDS const floatx4*>(b2s + (wc * K::MT + tt) * 16 + lg * 4);
         const int q = (wr + K::WR * i) * 16 + l16;
         r00[i] = (q / S) * K::TP + q % S;
       }
@@ -316,10 +318,9 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
 #pragma unroll
         for (int tt = 0; tt < K::MT; ++tt) {
           const int ch = (wc * K::MT + tt) * 16 + lg * 4;
-          const floatx4 bias = *reinterpret_cast<AS_LDS const floatx4*>(b2s + ch);
           bf16x4 o;
 #pragma unroll
-          for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][tt][v] + bias[v], 0.f);
+          for (int v = 0; v < 4; ++v) o[v] = (__bf16)fmaxf(acc[i][tt][v], 0.f);
           *reinterpret_cast<AS_LDS bf16x4*>(y2s + q * K::YROW + (((ch >> 3) ^ y2_key(q)) << 4) + (ch & 7) * 2) = o;
         }
       }
@@ -349,7 +350,9 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
 #pragma unroll
         for (int gg = 0; gg < K::G3; ++gg)
 #pragma unroll
-          for (int j = 0; j < K::NT3; ++j) acc[i][gg][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+          for (int j = 0; j < K::NT3; ++j)   // tile j of a group: channels (j >> 1) * 32 + lg * 8 + (j & 1) * 4 ..
+            acc[i][gg][j] = *reinterpret_cast<AS_LDS const floatx4*>(
+                b3s + (wc * K::G3 + gg) * 64 + (j >> 1) * 32 + lg * 8 + (j & 1) * 4);
 #pragma unroll
       for (int ks = 0; ks < K::KS2; ++ks) {
 #pragma unroll
@@ -375,14 +378,11 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
           const int chb = (wc * K::G3 + gg) * 64;          // first of the unit's 64 output channels
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            const int c8 = chb + t * 32 + lg * 8;
-            const floatx4 bia0 = *reinterpret_cast<AS_LDS const floatx4*>(b3s + c8);
-            const floatx4 bia1 = *reinterpret_cast<AS_LDS const floatx4*>(b3s + c8 + 4);
             bf16x8 o;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-              float r0 = (float)res[i][gg][t][v] + (acc[i][gg][2 * t][v] + bia0[v]);
-              float r1 = (float)res[i][gg][t][4 + v] + (acc[i][gg][2 * t + 1][v] + bia1[v]);
+              float r0 = (float)res[i][gg][t][v] + acc[i][gg][2 * t][v];
+              float r1 = (float)res[i][gg][t][4 + v] + acc[i][gg][2 * t + 1][v];
               if (POST_RELU) { r0 = fmaxf(r0, 0.f); r1 = fmaxf(r1, 0.f); }
               o[v] = (__bf16)r0;
               o[4 + v] = (__bf16)r1;
