@@ -549,17 +549,25 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_c
   };
 #pragma unroll
   for (int t = 0; t < RD; ++t) wload(t, t);
-  // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
-#pragma unroll
-  for (int pass = 0; pass < NPASS; ++pass) {
-    const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
-    // the residual is requested before the GEMM so that its latency hides behind it
-    bf16x8 xres[RB][NB / 2];
+  // The residual comes from HBM, the weights from L2, and a wave's loads complete in issue order:
+  // a weight fragment requested after a residual load cannot be used before that load has landed.
+  // So a pass's residual is requested as early as its registers allow, straight after the weights
+  // that are already due: for pass 0 here, for pass p+1 between the GEMM and the epilogue of pass p
+  // (the epilogue and the ring's depth then cover its latency).
+  bf16x8 xres[2][RB][NB / 2];
+  auto rload = [&](int pass) {
+    const int chb = (wc * K::NBT3 + pass * NB) * 16;
 #pragma unroll
     for (int i = 0; i < RB; ++i)
 #pragma unroll
       for (int j = 0; j < NB / 2; ++j)   // rows past the last pixel read pixel 0 (never stored)
-        xres[i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq[i], 0) * C + lane_channel(chb, NB, 2 * j, lg, 0));
+        xres[pass & 1][i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq[i], 0) * C + lane_channel(chb, NB, 2 * j, lg, 0));
+  };
+  rload(0);
+  // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
+#pragma unroll
+  for (int pass = 0; pass < NPASS; ++pass) {
+    const int chb = (wc * K::NBT3 + pass * NB) * 16;       // first channel of this wave's pass
     floatx4 acc[RB][NB];                                   // start at the bias
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
@@ -589,6 +597,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_c
         for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
       }
     }
+    if (pass + 1 < NPASS) rload(pass + 1);
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
       bf16x8 o[NB / 2];
@@ -598,7 +607,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_c
         for (int h = 0; h < 2; ++h) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            o[j / 2][h * 4 + v] = (__bf16)fmaxf((float)xres[i][j / 2][h * 4 + v] + acc[i][j + h][v], floor_);
+            o[j / 2][h * 4 + v] = (__bf16)fmaxf((float)xres[pass & 1][i][j / 2][h * 4 + v] + acc[i][j + h][v], floor_);
           }
         }
       }
@@ -680,11 +689,18 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
   const int te = (int)(((long long)(tile + 1) * nact) / nt);
   PHASE_MARK(0);
 
-  // the all-zero y1 row; the biases (phase 0's barriers come before their first use)
+  // the all-zero y1 row
   for (int i = tid; i < K::LDY / 8; i += K::NT)
     *reinterpret_cast<uint4*>(y1s + K::ZROW * K::LDY + i * 8) = uint4{0, 0, 0, 0};
-  for (int i = tid; i < K::M; i += K::NT) { b1s[i] = b1[i]; b2s[i] = b2[i]; }
-  for (int i = tid; i < K::C; i += K::NT) b3s[i] = b3[i];
+  // the biases go to LDS: requested here, stored once the first batch's cell ids (requested next)
+  // have been waited for anyway
+  constexpr int NBV = cdiv(2 * K::M + K::C, K::NT);
+  float bv[NBV];
+#pragma unroll
+  for (int u = 0; u < NBV; ++u) {
+    const int i = tid + u * K::NT;
+    bv[u] = i < K::M ? b1[i] : i < 2 * K::M ? b2[i - K::M] : i < 2 * K::M + K::C ? b3[i - 2 * K::M] : 0.f;
+  }
 
   for (int e0 = tb; e0 < te;) {
     // ---------------------------------------------------------------- phase 0
@@ -692,6 +708,11 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     int U;                                                 // unique window pixels = y1 rows
     // the batch's cell ids: one round of global loads, every later step reads them from LDS
     for (int i = tid; i < npb; i += K::NT) cellq[i] = idx ? idx[e0 + i] : e0 + i;
+    if (e0 == tb) {
+#pragma unroll
+      for (int u = 0; u < NBV; ++u)
+        if (tid + u * K::NT < 2 * K::M + K::C) b1s[tid + u * K::NT] = bv[u];   // b1 | b2 | b3 are contiguous
+    }
     for (;;) {
       for (int i = tid; i < K::HT; i += K::NT) hkey[i] = 0;
       if (tid == 0) misc[0] = 0;
