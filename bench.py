@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the fused kernel between L2 and the memory side, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's
 # plain copy kernel of known size (profiles/bench_stage3_b128_hbm_traffic_pmc.txt).
-MEASURED_TRAFFIC_BYTES = {"stage3_b128": 130921550}
+MEASURED_TRAFFIC_BYTES = {"stage3_b128": 113944232}   # at the workload's own ratio
 
 
 def parse_args():
@@ -222,6 +222,22 @@ def main():
     achieved_tflops = active_flops / fused_s / 1e12
     esize = 2 if cfg.dtype == "bf16" else 4
     x_bytes = cfg.N * cfg.H * cfg.W * cfg.C * esize
+    # Algorithmic bytes of one launch of the block kernel: every pixel some active patch's (S+2)x(S+2)
+    # window holds, read once; the active pixels written once; the weights once.
+    m_act = mask.cpu().numpy().astype(bool).reshape(cfg.N, cfg.G, cfg.GW)
+    pix_act = np.repeat(np.repeat(m_act, S, axis=1), S, axis=2)
+    pad = np.pad(pix_act, ((0, 0), (1, 1), (1, 1)))
+    pix_need = np.zeros_like(pix_act)
+    for dy in range(3):
+        for dx in range(3):
+            pix_need |= pad[:, dy:dy + cfg.H, dx:dx + cfg.W]
+    w_bytes = (2 * cfg.C * cfg.M + 9 * cfg.M * cfg.M) * esize
+    alg_bytes = (int(pix_need.sum()) + int(pix_act.sum())) * cfg.C * esize + w_bytes
+    achieved_gbs = alg_bytes / fused_s / 1e9
+    kernel_name = ("bottleneck_generic_kernel" if packed is None else
+                   "stream_bneck_kernel" if (cfg.C, cfg.M, S) == (256, 64, 8) else "fused_bneck_kernel")
+    # the bound is whichever ideal time is longer: active FLOPs at the MFMA peak or these bytes at the HBM peak
+    hbm_bound = alg_bytes / (PEAK_HBM_GBS * 1e9) > active_flops / (PEAK_BF16_TFLOPS * 1e12)
     dense_best = dense_t["mean_ms"] if dense_packed_ms is None else dense_packed_ms
     if torch_dense and "mean_ms" in torch_dense:
         dense_best = min(dense_best, torch_dense["mean_ms"])
@@ -314,10 +330,16 @@ def main():
                        "dense_own": dense_t, "dense_own_prepacked_loop_ms": dense_packed_ms,
                        "fused_block_loop_ms": fused_loop_ms, "dense_torch_miopen": torch_dense},
         "hbm_floor_ms": 2 * x_bytes / (PEAK_HBM_GBS * 1e9) * 1e3,
-        "roofline": {"bound": "mfma", "kernel": "fused_bneck_kernel", "achieved": achieved_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                     "active_flops_per_launch": active_flops, "avg_launch_ms": fused_loop_ms,
+        "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": kernel_name,
+                     "achieved": achieved_gbs if hbm_bound else achieved_tflops,
+                     "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
+                     "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                     "frac": achieved_gbs / PEAK_HBM_GBS if hbm_bound else achieved_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.ratio is None else None,
+                     "active_flops_per_launch": active_flops, "algorithmic_bytes_per_launch": alg_bytes,
+                     "frac_of_mfma_peak": achieved_tflops / PEAK_BF16_TFLOPS,
+                     "frac_of_hbm_peak": achieved_gbs / PEAK_HBM_GBS,
+                     "avg_launch_ms": fused_loop_ms,
                      "avg_launch_ms_single_event_pairs": fused_t["mean_ms"], "launches_timed": reps},
         "cpu_baseline": cpu,
     }
