@@ -191,6 +191,68 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
   }
 }
 
+// The common case (a patch row is exactly 4 KiB, S in {2, 4, 8}: every ResNet stage in bf16) with the
+// cell split by rows over WPC waves of the workgroup: a wave takes two rows (8 KiB, eight 16-byte
+// pieces per lane), keeps them in registers, and the waves of a cell add their partial sums in a
+// fixed order through LDS.  An inactive cell is then written to pass_out from those registers: x is
+// read once, and because a wave's share is small and there are WPC times more waves, the reading of
+// some cells overlaps the writing of others (with a whole 32 KiB cell per wave, all waves first
+// read, then all wrote: the two halves of the traffic did not overlap).
+template <typename T, int WPC>
+__global__ __launch_bounds__(kMaskerThreads) void masker_rows_kernel(
+    const T* __restrict__ x, const float* __restrict__ Wm, double bm, double thr, int H, int W,
+    int C, int G, int GW, int P, uint8_t* __restrict__ mask, double* __restrict__ logits,
+    T* __restrict__ pass_out) {
+  constexpr int S = 2 * WPC;
+  constexpr int V = 16 / (int)sizeof(T);
+  constexpr int CPB = kCellsPerBlock / WPC;   // cells per workgroup
+  __shared__ double part[kCellsPerBlock];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cell = blockIdx.x * CPB + wave / WPC, sub = wave % WPC;
+  const bool valid = cell < P;                // wave-uniform; every wave reaches the barrier
+  const int cc = valid ? cell : 0;
+  const int n = cc / (G * GW);
+  const int rem = cc - n * (G * GW);
+  const int gy = rem / GW, gx = rem - gy * GW;
+  const size_t pitch = (size_t)W * C;
+  const size_t off = ((size_t)(n * H + gy * S + 2 * sub) * W + (size_t)gx * S) * C + (size_t)lane * V;
+  uint4 q[2][4];
+#pragma unroll
+  for (int r = 0; r < 2; ++r)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) q[r][u] = *reinterpret_cast<const uint4*>(x + off + r * pitch + u * 64 * V);
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int c = ((lane + 64 * u) * V) % C;
+    const float4 w0 = *reinterpret_cast<const float4*>(Wm + c);
+    const float4 w1 = V == 8 ? *reinterpret_cast<const float4*>(Wm + c + 4) : float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < 2; ++r) fma_piece(acc[u], q[r][u], w0, w1, T{});
+  }
+  double tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  if constexpr (WPC > 1) {
+    if (lane == 0) part[wave] = tot;
+    __syncthreads();
+    tot = 0.0;
+#pragma unroll
+    for (int k = 0; k < WPC; ++k) tot += part[wave / WPC * WPC + k];   // the same order in every wave of the cell
+  }
+  const double logit = bm + tot / (double)(S * S);
+  const bool on = logit > thr;
+  if (!valid) return;
+  if (lane == 0 && sub == 0) {
+    if (logits) logits[cell] = logit;
+    if (mask) mask[cell] = on ? 1 : 0;
+  }
+  if (pass_out != nullptr && !on) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) store_nt16(pass_out + off + r * pitch + u * 64 * V, q[r][u]);
+  }
+}
+
 // Ordered stream compaction by one workgroup.  A thread takes V consecutive cells (one 8-byte
 // load when V = 8), a shuffle scan over the per-thread counts gives each thread its rank
 // inside its wave, a scan over the 16 wave totals its rank inside the 1024*V-cell round, and
@@ -263,8 +325,22 @@ hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int 
   hipLaunchKernelGGL((masker_logit_kernel<T, VEC, HOIST>), grid, block, 0, st, (const T*)x.data, \
                      Wm, (double)bm, (double)thr, S, x.h, x.w, x.c, G, GW, P, mask, logits,      \
                      (T*)pass_out)
+#define LASNET_MASKER_ROWS(T, WPC)                                                               \
+  hipLaunchKernelGGL((masker_rows_kernel<T, WPC>), dim3((P + kCellsPerBlock / WPC - 1) / (kCellsPerBlock / WPC)), \
+                     block, 0, st, (const T*)x.data, Wm, (double)bm, (double)thr, x.h, x.w, x.c, G, GW, P,     \
+                     mask, logits, (T*)pass_out)
   if (P == 0) {
     // empty batch: nothing to pool; the compaction below still writes count = 0
+  } else if (hoist && (S == 2 || S == 4 || S == 8)) {
+    if (x.dtype == LASNET_BF16) {
+      if (S == 2) LASNET_MASKER_ROWS(uint16_t, 1);
+      else if (S == 4) LASNET_MASKER_ROWS(uint16_t, 2);
+      else LASNET_MASKER_ROWS(uint16_t, 4);
+    } else {
+      if (S == 2) LASNET_MASKER_ROWS(float, 1);
+      else if (S == 4) LASNET_MASKER_ROWS(float, 2);
+      else LASNET_MASKER_ROWS(float, 4);
+    }
   } else if (x.dtype == LASNET_BF16) {
     if (hoist) LASNET_MASKER_LAUNCH(uint16_t, true, true);
     else if (vec) LASNET_MASKER_LAUNCH(uint16_t, true, false);
@@ -275,6 +351,7 @@ hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int 
     else LASNET_MASKER_LAUNCH(float, false, false);
   }
 #undef LASNET_MASKER_LAUNCH
+#undef LASNET_MASKER_ROWS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (count) {
