@@ -49,7 +49,6 @@ struct StreamCfg {
   static constexpr int MAXQ = 64;                           // list entries one workgroup takes
   static constexpr int XGRP = R1 / 2;                       // 1 KiB pieces (two x rows) of a window
   static constexpr int NXL = XGRP / NW;                     // x loads per wave per patch
-  static constexpr int NST = 2 * RB2 * G3;                  // store instructions per wave per patch
   static constexpr int OFF_XS = 0, XS_BYTES = 2 * R1 * XROW;
   static constexpr int OFF_Y1 = OFF_XS + XS_BYTES, Y1_BYTES = Y1ROWS * YROW;
   static constexpr int OFF_Y2 = OFF_Y1 + Y1_BYTES, Y2_BYTES = Q * YROW;
@@ -204,10 +203,10 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
   for (int p = 0; p < npat; ++p) {
     AS_LDS const char* xc = xs + (p & 1) * (K::R1 * K::XROW);
     AS_LDS const int* pix = pixs + (p % 3) * (2 * K::R1);
-    // The window of entry p has landed (requested a whole patch ago) and every wave has left the
-    // previous patch.  A wave's global-memory operations complete in issue order: only the
-    // previous patch's NST stores are younger than the loads of this window and may stay in flight.
-    if (p == 0) barrier_keep_vm<0>(); else barrier_keep_vm<K::NST>();
+    // The window of entry p has landed (requested a whole patch ago), the previous patch's stores
+    // are done and every wave has left the previous patch.  (Letting those stores stay in flight
+    // here measured the same.)
+    barrier_keep_vm<0>();
     if (p + 1 < npat) issue_x(p + 1);
     STREAM_MARK(0);
 
