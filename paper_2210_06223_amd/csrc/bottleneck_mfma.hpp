@@ -855,18 +855,25 @@ hipError_t pack_one(const void* W1, const void* W2, const void* W3, void* packed
   return hipGetLastError();
 }
 
+// A kernel that needs more than 64 KiB of dynamic LDS must be told so once per device.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;    // devices past 63: set every time
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 template <class K>
 hipError_t launch_one(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
                       const void* packed, const float* b1, const float* b2, const float* b3,
                       void* out, bool post_relu, hipStream_t st) {
   auto k = fused_bneck_kernel<K>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       K::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> lds_allowed{0};
+  if (hipError_t e = allow_dynamic_lds((const void*)k, K::LDS_BYTES, lds_allowed); e != hipSuccess) return e;
   const int slots = device_cu_count() * ((160 * 1024) / K::LDS_BYTES);
   int grid = (g.P + K::PPW - 1) / K::PPW;
   grid = (grid + slots - 1) / slots * slots;

@@ -422,13 +422,9 @@ hipError_t launch_stream(const Geom& g, const void* x, const int32_t* idx, const
                          void* out, bool post_relu, hipStream_t st) {
   if ((size_t)g.N * g.H * g.W * K::C * 2 > ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit offsets
   auto k = post_relu ? stream_bneck_kernel<K, true> : stream_bneck_kernel<K, false>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[post_relu]) {
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       K::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[post_relu] = true;
-  }
+  static std::atomic<unsigned long long> lds_allowed[2];
+  if (hipError_t e = allow_dynamic_lds((const void*)k, K::LDS_BYTES, lds_allowed[post_relu]); e != hipSuccess)
+    return e;
   // one persistent workgroup per CU; more only when a run would exceed what a workgroup stages
   int grid = device_cu_count();
   const int need = (g.P + K::MAXQ - 1) / K::MAXQ;
