@@ -59,8 +59,8 @@ def parse_args():
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by image with no exchange; "
-              "see DESIGN.md). --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path shards by image with no exchange: "
+              "each GPU would run its own images). --gpus %d is not supported." % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
