@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0
 
 # Bytes per launch of the fused kernel between L2 and the memory side, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's
-# plain copy kernel of known size (profiles/bench_stage3_b128_hbm_traffic_pmc.txt).
-MEASURED_TRAFFIC_BYTES = {"stage3_b128": 113952097}   # at the workload's own ratio
+# plain copy kernel of known size (profiles/bench_<workload>_hbm_traffic_pmc.txt).
+MEASURED_TRAFFIC_BYTES = {"stage3_b128": 113952097, "stage1_b64": 96091086}   # at the workload's own ratio
 
 
 def parse_args():
