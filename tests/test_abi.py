@@ -108,3 +108,13 @@ def test_product_path_never_touches_the_oracle():
     uses = [i for i, line in enumerate(bench.splitlines()) if re.search(r"\bimport\b.*\boracle\b|from oracle", line)]
     start = bench.splitlines().index("def cpu_baseline(cfg, inp, bm):")
     assert uses and all(i > start for i in uses)
+
+
+def test_flag_and_status_values_match_the_header():
+    text = open(os.path.join(ROOT, "include", "lasnet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    vals = {k: int(v) for k, v in re.findall(r"\b(LASNET_[A-Z0-9_]+)\s*=\s*(-?\d+)", text)}
+    for name in ("LASNET_OK", "LASNET_EINVAL", "LASNET_ESHAPE", "LASNET_EUNSUPPORTED", "LASNET_EALIAS", "LASNET_EHIP",
+                 "LASNET_F32", "LASNET_BF16", "LASNET_POST_RELU", "LASNET_FORCE_GENERIC", "LASNET_SKIP_IDENTITY"):
+        assert name in vals, name
+        assert getattr(B, name) == vals[name], name
