@@ -310,7 +310,8 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
   // Direct global->LDS load as inline asm: the compiler must not know that it writes LDS,
   // or it makes every LDS read that follows wait for ALL outstanding global-memory
   // operations (it cannot prove the stages disjoint) and the stream stops being a stream.
-  // Completion is tracked by hand instead: see the barrier in the chunk loop.
+  // Completion is tracked by hand instead: see the barrier in the chunk loop.  (m0, which carries
+  // the LDS address, is a reserved register: the compiler never keeps a value in it across statements.)
   auto issue_x = [&](int ch) {
     const int stage = ch % K::NSTG;
 #pragma unroll
