@@ -15,8 +15,15 @@
  *   - Calls enqueue work on `hip_stream` (a hipStream_t, NULL = default stream) and
  *     return without synchronising.  `count` is read on the device: there is no host
  *     round trip between lasnet_masker and lasnet_sparse_bottleneck.
- *   - Return value: LASNET_OK or a negative lasnet_status.  On error nothing has been
- *     enqueued and no output buffer has been touched.
+ *   - Return value: LASNET_OK or a negative lasnet_status.  Arguments are checked, and the
+ *     host-side set-up that can fail is done, before the first launch: with any status other than
+ *     LASNET_EHIP nothing has been enqueued and no output buffer has been touched.  LASNET_EHIP
+ *     reports a failure of the HIP runtime itself (no device, a launch that was refused); the
+ *     contents of the output buffers are then unspecified.
+ *   - Alignment: none is required.  The matrix-core kernels move 16 bytes per lane, so they
+ *     are used only when x, out and the weight buffers are 16-byte aligned (device allocations
+ *     are); other pointers are served by the slower shape-generic kernel (lasnet_*_packed, which
+ *     has no such fallback, returns LASNET_EUNSUPPORTED).
  *   - A process that has no usable gfx950 device gets LASNET_EHIP from every compute
  *     call; there is no CPU fallback.
  */
@@ -114,8 +121,9 @@ LASNET_API int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, flo
  *   out = x + (b3 + y2 . W3^T)                         W3 [C][M]        no ReLU before the add
  * Every other pixel: out = x, bit for bit.  Neighbour pixels that belong to inactive
  * patches still feed y1 with their true x.  The result does not depend on the order of
- * idx; entries must be unique and < N*G*GW (not checked).  idx == NULL means "all cells
- * active" and count is then ignored (may be NULL).
+ * idx; entries must be unique (not checked).  An entry that is not a cell of this map
+ * (negative, or >= N*G*GW) is ignored; a count[0] beyond N*G*GW is read as N*G*GW.
+ * idx == NULL means "all cells active" and count is then ignored (may be NULL).
  *
  * M: bottleneck width.  out: same shape and dtype as x, a different buffer: out->data ==
  * x->data gives LASNET_EALIAS, because a patch updated in place would corrupt the
@@ -143,9 +151,12 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
  * buffer in which the weights are laid out fragment by fragment in the order the waves
  * consume them.  lasnet_sparse_bottleneck[_ex] and lasnet_dense_bottleneck take the plain
  * tensors and repack them on every call, on the caller's stream, into device memory the
- * library owns (one buffer per device and stream, allocated with hipMalloc on first use
- * and kept until the process ends -- so those entry points cannot be stream-captured on
- * their first call).  Weights of an inference model do not change, so a caller can instead
+ * library owns: one buffer per device and stream, allocated with hipMalloc (the only call of
+ * these entry points that may block) on first use and again when a shape needs a larger one --
+ * the smaller buffer is then kept, not freed, because enqueued work may still read it; at most
+ * 8.5 MiB each, all kept until the process ends.  So those entry points cannot be
+ * stream-captured before the stream's buffer has its final size.
+ * Weights of an inference model do not change, so a caller can instead
  * repack once, like it folded BN once (Sec. 3.4), and pass the result to
  * lasnet_sparse_bottleneck_packed, which allocates nothing:
  *   bytes = lasnet_packed_weights_bytes(dtype, C, M, S)   host query; 0 = this shape has no

@@ -91,15 +91,22 @@ def upsample_mask(mask, S):
     return np.repeat(np.repeat(m, S, axis=1), S, axis=2)
 
 
-def sparse_bottleneck(x, mask, S, W1, b1, W2, b2, W3, b3, post_relu=False):
-    """out = x + up_S(mask) * F(x): unselected regions keep the input (Sec. 3.1)."""
+def masked_output(x, f, mask, S, post_relu=False):
+    """out = x + up_S(mask) * f for a residual branch f = F(x) computed beforehand (F does not
+    depend on the mask, so tests that try many masks on one input compute it once)."""
     x = _f64(x)
-    f, _, _ = residual_branch(x, W1, b1, W2, b2, W3, b3)
     up = upsample_mask(mask, S).astype(bool)[..., None]
     y = x + f
     if post_relu:
         y = np.maximum(y, 0.0)
     return np.where(up, y, x)
+
+
+def sparse_bottleneck(x, mask, S, W1, b1, W2, b2, W3, b3, post_relu=False):
+    """out = x + up_S(mask) * F(x): unselected regions keep the input (Sec. 3.1)."""
+    x = _f64(x)
+    f, _, _ = residual_branch(x, W1, b1, W2, b2, W3, b3)
+    return masked_output(x, f, mask, S, post_relu)
 
 
 def dense_bottleneck(x, W1, b1, W2, b2, W3, b3, post_relu=False):

@@ -40,43 +40,48 @@ class lasnet_tensor(ctypes.Structure):
                 ("w", ctypes.c_int32), ("c", ctypes.c_int32), ("dtype", ctypes.c_int32)]
 
 
+def load_library(path: str) -> ctypes.CDLL:
+    """Loads one build of the library and declares the argument types of its entry points."""
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "liblasnet.so is not built (%s missing): run `python -m paper_2210_06223_amd.build`; "
+            "there is no CPU fallback" % path)
+    L = ctypes.CDLL(path)
+    vp, ip, tp = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(lasnet_tensor)
+    L.lasnet_version.restype = ip
+    L.lasnet_version.argtypes = []
+    L.lasnet_status_string.restype = ctypes.c_char_p
+    L.lasnet_status_string.argtypes = [ip]
+    L.lasnet_masker.restype = ip
+    L.lasnet_masker.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, vp]
+    L.lasnet_masker_ex.restype = ip
+    L.lasnet_masker_ex.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, tp, vp]
+    L.lasnet_masker_logits.restype = ip
+    L.lasnet_masker_logits.argtypes = [tp, vp, ctypes.c_float, ip, vp, vp]
+    L.lasnet_sparse_bottleneck.restype = ip
+    L.lasnet_sparse_bottleneck.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp, vp]
+    L.lasnet_sparse_bottleneck_ex.restype = ip
+    L.lasnet_sparse_bottleneck_ex.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp,
+                                              ctypes.c_uint32, vp]
+    L.lasnet_dense_bottleneck.restype = ip
+    L.lasnet_dense_bottleneck.argtypes = [tp, ip, vp, vp, vp, vp, vp, vp, tp, ctypes.c_uint32, vp]
+    L.lasnet_has_fast_path.restype = ip
+    L.lasnet_has_fast_path.argtypes = [ip, ip, ip, ip]
+    L.lasnet_packed_weights_bytes.restype = ctypes.c_size_t
+    L.lasnet_packed_weights_bytes.argtypes = [ip, ip, ip, ip]
+    L.lasnet_pack_weights.restype = ip
+    L.lasnet_pack_weights.argtypes = [ip, ip, ip, ip, vp, vp, vp, vp, vp]
+    L.lasnet_sparse_bottleneck_packed.restype = ip
+    L.lasnet_sparse_bottleneck_packed.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, tp,
+                                                  ctypes.c_uint32, vp]
+    return L
+
+
 def lib() -> ctypes.CDLL:
-    """Loads liblasnet.so (built by paper_2210_06223_amd.build / __graft_entry__.build)."""
+    """The in-tree liblasnet.so (built by paper_2210_06223_amd.build / __graft_entry__.build)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise RuntimeError(
-                "liblasnet.so is not built (%s missing): run `python -m paper_2210_06223_amd.build`; "
-                "there is no CPU fallback" % _LIB_PATH)
-        L = ctypes.CDLL(_LIB_PATH)
-        vp, ip, tp = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(lasnet_tensor)
-        L.lasnet_version.restype = ip
-        L.lasnet_version.argtypes = []
-        L.lasnet_status_string.restype = ctypes.c_char_p
-        L.lasnet_status_string.argtypes = [ip]
-        L.lasnet_masker.restype = ip
-        L.lasnet_masker.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, vp]
-        L.lasnet_masker_ex.restype = ip
-        L.lasnet_masker_ex.argtypes = [tp, vp, ctypes.c_float, ip, ctypes.c_float, vp, vp, vp, tp, vp]
-        L.lasnet_masker_logits.restype = ip
-        L.lasnet_masker_logits.argtypes = [tp, vp, ctypes.c_float, ip, vp, vp]
-        L.lasnet_sparse_bottleneck.restype = ip
-        L.lasnet_sparse_bottleneck.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp, vp]
-        L.lasnet_sparse_bottleneck_ex.restype = ip
-        L.lasnet_sparse_bottleneck_ex.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp,
-                                                  ctypes.c_uint32, vp]
-        L.lasnet_dense_bottleneck.restype = ip
-        L.lasnet_dense_bottleneck.argtypes = [tp, ip, vp, vp, vp, vp, vp, vp, tp, ctypes.c_uint32, vp]
-        L.lasnet_has_fast_path.restype = ip
-        L.lasnet_has_fast_path.argtypes = [ip, ip, ip, ip]
-        L.lasnet_packed_weights_bytes.restype = ctypes.c_size_t
-        L.lasnet_packed_weights_bytes.argtypes = [ip, ip, ip, ip]
-        L.lasnet_pack_weights.restype = ip
-        L.lasnet_pack_weights.argtypes = [ip, ip, ip, ip, vp, vp, vp, vp, vp]
-        L.lasnet_sparse_bottleneck_packed.restype = ip
-        L.lasnet_sparse_bottleneck_packed.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, tp,
-                                                      ctypes.c_uint32, vp]
-        _lib = L
+        _lib = load_library(_LIB_PATH)
     return _lib
 
 

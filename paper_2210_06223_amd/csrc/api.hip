@@ -10,9 +10,11 @@ using namespace lasnet;
 namespace {
 
 // Device memory the library owns: one buffer per (device, stream) for the repacked weights
-// of calls that pass raw W1/W2/W3.  Grown on demand, kept until the process ends.  Work on
-// one stream is ordered, so calls on the same stream may share it; calls on different
-// streams get different buffers.
+// of calls that pass raw W1/W2/W3.  Work on one stream is ordered, so calls on the same stream
+// may share it; calls on different streams get different buffers.  A buffer that turns out too
+// small is not freed (work already enqueued may still read it): a larger one is allocated beside
+// it and the old one is kept until the process ends.  Shapes with a matrix-core kernel need at
+// most 8.5 MiB, so what accumulates is bounded by a few buffers of that size per stream.
 struct Workspace { void* ptr = nullptr; size_t cap = 0; };
 std::mutex g_ws_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
@@ -23,17 +25,12 @@ void* get_workspace(hipStream_t st, size_t bytes) {
   std::lock_guard<std::mutex> lock(g_ws_mu);
   Workspace& w = g_ws[std::make_pair(dev, st)];
   if (w.cap < bytes) {
-    if (w.ptr) {
-      if (hipStreamSynchronize(st) != hipSuccess) return nullptr;   // earlier calls still read it
-      (void)hipFree(w.ptr);
-      w.ptr = nullptr;
-      w.cap = 0;
-    }
-    if (hipMalloc(&w.ptr, bytes) != hipSuccess) {
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
       (void)hipGetLastError();
-      w.ptr = nullptr;
       return nullptr;
     }
+    w.ptr = p;                                   // the previous buffer, if any, stays allocated
     w.cap = bytes;
   }
   return w.ptr;
@@ -69,11 +66,12 @@ int dense_tile(int dtype, int H, int W, int C, int M, bool force_generic) {
   return 0;
 }
 
-// packed != nullptr: the caller passes repacked weights (W1..W3 unused).
+// packed != nullptr: the caller passes repacked weights (W1..W3 unused).  scratch != nullptr: raw weights
+// are repacked into that buffer of scratch_bytes instead of the library's per-stream one.
 int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S, int M,
               const void* W1, const float* b1, const void* W2, const float* b2, const void* W3,
               const float* b3, const void* packed, lasnet_tensor* out, uint32_t flags, bool dense,
-              void* stream) {
+              void* stream, void* scratch = nullptr, size_t scratch_bytes = 0) {
   int s = check_tensor(x);
   if (s != LASNET_OK) return s;
   if (!out) return LASNET_EINVAL;
@@ -94,7 +92,17 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   }
   if (S <= 0) return LASNET_EINVAL;
   if (x->h % S != 0 || x->w % S != 0) return LASNET_ESHAPE;
-  const bool fast = x->dtype == LASNET_BF16 && !force_generic && mfma_supported(x->c, M, S);
+  const size_t map_bytes = (size_t)x->n * x->h * x->w * x->c * (x->dtype == LASNET_BF16 ? 2 : 4);
+  // The matrix-core kernels move 16 bytes per lane: x, out and the packed weights must be 16-byte
+  // aligned for them (C is a multiple of 64 there, so every pixel then is).  Anything else, and maps
+  // beyond a kernel's own addressing limit, go to the generic kernel.
+  bool fast = x->dtype == LASNET_BF16 && !force_generic && mfma_supported(x->c, M, S);
+  if (fast) {
+    const size_t lim = mfma_max_map_bytes(x->c, M, S);
+    uintptr_t low = (uintptr_t)x->data | (uintptr_t)out->data | (uintptr_t)packed;
+    if (!packed) low |= (uintptr_t)W1 | (uintptr_t)W2 | (uintptr_t)W3;     // the repack reads 16-byte pieces
+    if ((low & 15) != 0 || (lim != 0 && map_bytes > lim)) fast = false;
+  }
   if (packed && !fast) return LASNET_EUNSUPPORTED;
   if (!fast && !generic_fits(M, S)) return LASNET_EUNSUPPORTED;
   if (!device_ok()) return LASNET_EHIP;
@@ -105,17 +113,26 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   g.G = x->h / S; g.GW = x->w / S; g.P = x->n * g.G * g.GW;
   const BlockWeights w{W1, b1, W2, b2, W3, b3};
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = hipSuccess;
+  // Everything that can fail on the host comes before the first launch: kernel attributes, then the
+  // buffer for the repacked weights (the caller's, the library's per stream, or `scratch`).
+  hipError_t e = fast ? prepare_mfma(x->c, M, S) : prepare_generic(x->dtype);
+  if (e != hipSuccess) return LASNET_EHIP;
   if (fast && !packed) {
-    void* ws = get_workspace(st, mfma_packed_bytes(x->c, M, S));
-    if (!ws) return LASNET_EHIP;
+    const size_t need = mfma_packed_bytes(x->c, M, S);
+    void* ws = nullptr;
+    if (scratch) {
+      if (need > scratch_bytes) return LASNET_EUNSUPPORTED;
+      ws = scratch;
+    } else {
+      ws = get_workspace(st, need);
+      if (!ws) return LASNET_EHIP;
+    }
     e = launch_pack(x->c, M, S, W1, W2, W3, ws, st);
     if (e != hipSuccess) return LASNET_EHIP;
     packed = ws;
   }
   if (!dense && idx && !(flags & LASNET_SKIP_IDENTITY)) {
-    const size_t bytes = (size_t)x->n * x->h * x->w * x->c * (x->dtype == LASNET_BF16 ? 2 : 4);
-    e = launch_copy(x->data, out->data, bytes, st);
+    e = launch_copy(x->data, out->data, map_bytes, st);
     if (e != hipSuccess) return LASNET_EHIP;
   }
   const bool relu = (flags & LASNET_POST_RELU) != 0;

@@ -38,6 +38,7 @@ __global__ __launch_bounds__(kGenThreads) void bneck_generic_kernel(
   const int nact = idx ? min(*count, g.P) : g.P;
   for (int e = blockIdx.x; e < nact; e += gridDim.x) {
     const int cell = idx ? idx[e] : e;
+    if ((unsigned)cell >= (unsigned)g.P) continue;           // not a cell of this map (uniform over the workgroup)
     const int n = cell / (g.G * g.GW);
     const int rem = cell - n * (g.G * g.GW);
     const int gy = rem / g.GW, gx = rem - gy * g.GW;
@@ -121,28 +122,37 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st_
   return hipGetLastError();
 }
 
+// The kernels take up to kLdsLimit bytes of dynamic LDS: said once per device and kernel.
+hipError_t prepare_generic(int dtype) {
+  static std::atomic<unsigned long long> done[2];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const int which = dtype == LASNET_BF16 ? 1 : 0;
+  const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;
+  if (done[which].load(std::memory_order_acquire) & bit) return hipSuccess;
+  const void* k = which ? (const void*)bneck_generic_kernel<uint16_t> : (const void*)bneck_generic_kernel<float>;
+  e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  if (e == hipSuccess) done[which].fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 hipError_t launch_generic(int dtype, const Geom& g, const void* x, const int32_t* idx,
                           const int32_t* count, const BlockWeights& w, void* out, bool post_relu,
                           hipStream_t st_) {
   if (g.P == 0) return hipSuccess;
   const size_t lds = generic_lds_bytes(g.M, g.S);
   if (lds > kLdsLimit) return hipErrorInvalidValue;
+  if (hipError_t e = prepare_generic(dtype); e != hipSuccess) return e;
   const int grid = g.P < 256 * 16 ? g.P : 256 * 16;
-  hipError_t e;
   if (dtype == LASNET_BF16) {
-    auto k = bneck_generic_kernel<uint16_t>;
-    e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k, dim3(grid), dim3(kGenThreads), lds, st_, g, (const uint16_t*)x, idx,
-                       count, (const uint16_t*)w.W1, w.b1, (const uint16_t*)w.W2, w.b2,
-                       (const uint16_t*)w.W3, w.b3, (uint16_t*)out, (int)post_relu);
+    hipLaunchKernelGGL(bneck_generic_kernel<uint16_t>, dim3(grid), dim3(kGenThreads), lds, st_, g,
+                       (const uint16_t*)x, idx, count, (const uint16_t*)w.W1, w.b1, (const uint16_t*)w.W2,
+                       w.b2, (const uint16_t*)w.W3, w.b3, (uint16_t*)out, (int)post_relu);
   } else {
-    auto k = bneck_generic_kernel<float>;
-    e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k, dim3(grid), dim3(kGenThreads), lds, st_, g, (const float*)x, idx, count,
-                       (const float*)w.W1, w.b1, (const float*)w.W2, w.b2, (const float*)w.W3,
-                       w.b3, (float*)out, (int)post_relu);
+    hipLaunchKernelGGL(bneck_generic_kernel<float>, dim3(grid), dim3(kGenThreads), lds, st_, g,
+                       (const float*)x, idx, count, (const float*)w.W1, w.b1, (const float*)w.W2, w.b2,
+                       (const float*)w.W3, w.b3, (float*)out, (int)post_relu);
   }
   return hipGetLastError();
 }

@@ -34,6 +34,16 @@ int device_cu_count() {
 
 bool mfma_supported(int C, int M, int S) { return find_variant(C, M, S) != nullptr; }
 
+size_t mfma_max_map_bytes(int C, int M, int S) {
+  const MfmaVariant* v = find_variant(C, M, S);
+  return v ? v->max_map_bytes : 0;
+}
+
+hipError_t prepare_mfma(int C, int M, int S) {
+  const MfmaVariant* v = find_variant(C, M, S);
+  return v ? v->prepare() : hipErrorInvalidValue;
+}
+
 size_t mfma_packed_bytes(int C, int M, int S) {
   const MfmaVariant* v = find_variant(C, M, S);
   return v ? v->packed_bytes : 0;

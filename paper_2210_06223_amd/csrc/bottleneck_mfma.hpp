@@ -33,20 +33,6 @@
 namespace lasnet {
 namespace {
 
-#ifdef LASNET_PHASE_CLOCKS
-__device__ long long g_phase_clk[6 * 2048];
-#define PHASE_MARK(i)                                                            \
-  do {                                                                           \
-    if (threadIdx.x == 0 && blockIdx.x < 2048) {                                 \
-      g_phase_clk[blockIdx.x * 6 + (i)] = wall_clock64();                        \
-      if ((i) == 0) g_phase_clk[blockIdx.x * 6 + 5] = clock64();                 \
-      if ((i) == 4) g_phase_clk[blockIdx.x * 6 + 5] = clock64() - g_phase_clk[blockIdx.x * 6 + 5]; \
-    }                                                                            \
-  } while (0)
-#else
-#define PHASE_MARK(i) do { } while (0)
-#endif
-
 __device__ inline floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
@@ -202,10 +188,17 @@ __device__ __forceinline__ void dispatch_count(int n, F&& f) {
 // Workgroup barrier that waits for this wave's LDS traffic and for all but the youngest VM
 // of its global-memory operations -- NOT for all of them, as __syncthreads() would: the
 // x chunks and weights already requested for later steps stay in flight across it.
+// Built with LASNET_DRAIN_AT_BARRIERS (the check build of the library) every such barrier waits for
+// ALL of the wave's global-memory operations instead: slower, and independent of the hand-made
+// count.  The tests compare the two builds bit for bit.
 template <int VM>
 __device__ __forceinline__ void barrier_keep_vm() {
   static_assert(VM >= 0 && VM < 64, "vmcnt is 6 bits");
+#ifdef LASNET_DRAIN_AT_BARRIERS
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#else
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+#endif
 }
 
 // The same with a count that is a constant only after unrolling (folds to one of the cases).
@@ -688,7 +681,6 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
   const int tile = xcd * (nt >> 3) + min(xcd, nt & 7) + jx;   // jx < runs of this XCD because b < nt
   const int tb = (int)(((long long)tile * nact) / nt);
   const int te = (int)(((long long)(tile + 1) * nact) / nt);
-  PHASE_MARK(0);
 
   // the all-zero y1 row
   for (int i = tid; i < K::LDY / 8; i += K::NT)
@@ -725,7 +717,8 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
         const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
-        if (h >= 0 && h < g.H && w >= 0 && w < g.W) {
+        // (a list entry that is not a cell of this map claims nothing and stores nothing)
+        if ((unsigned)cell < (unsigned)g.P && h >= 0 && h < g.H && w >= 0 && w < g.W) {
           const int key = (n * g.H + h) * g.W + w + 1;
           unsigned s = hash_pix(key) & (K::HT - 1);
           for (;;) {
@@ -753,7 +746,7 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
       npb = max(1, min(npb - 1, npb * K::R1MAX / U));
       __syncthreads();
     }
-    const int nblk1 = (U + 15) >> 4;
+    const int nblk1 = max(1, (U + 15) >> 4);              // (U = 0 only if every entry of the batch was invalid)
     const int nq = npb * S * S, nblk2 = (nq + 15) >> 4;
     // (c) row of every window position; pixel of every output row
     for (int t = tid; t < npb * WW; t += K::NT) {
@@ -763,7 +756,7 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
       const int gy = rem / g.GW, gx = rem - gy * g.GW;
       const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
       int row = K::ZROW;
-      if (h >= 0 && h < g.H && w >= 0 && w < g.W) {
+      if ((unsigned)cell < (unsigned)g.P && h >= 0 && h < g.H && w >= 0 && w < g.W) {
         const int key = (n * g.H + h) * g.W + w + 1;
         unsigned s = hash_pix(key) & (K::HT - 1);
         while (hkey[s] != key) s = (s + 1) & (K::HT - 1);
@@ -774,7 +767,8 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     __syncthreads();                                       // rowpix[0] is final
     // rows up to the block count conv1 really runs (rounded up to its wave rows) must name
     // a valid pixel: their x is loaded and convolved, the result is never used
-    for (int r = U + tid; r < (nblk1 + K::WR1 - 1) / K::WR1 * K::WR1 * 16; r += K::NT) rowpix[r] = rowpix[0];
+    const int pad_pix = U > 0 ? rowpix[0] : 0;
+    for (int r = U + tid; r < (nblk1 + K::WR1 - 1) / K::WR1 * K::WR1 * 16; r += K::NT) rowpix[r] = pad_pix;
     for (int q = tid; q < K::R2P; q += K::NT) {
       int pix = -1;
       if (q < nq) {
@@ -782,12 +776,11 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
         const int cell = cellq[slot];
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
-        pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
+        if ((unsigned)cell < (unsigned)g.P) pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
       }
       pixq[q] = pix;
     }
     __syncthreads();
-    PHASE_MARK(1);
 
     // Row blocks are dealt to the wave rows round-robin (wave row wr takes blocks wr, wr+WR,
     // ...); the count is rounded up to a multiple of WR, the extra blocks compute unused rows.
@@ -796,14 +789,12 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
                                                    (l_bf16_p)xs, (l_bf16_p)y1s, tid, wave);
     });
     __syncthreads();
-    PHASE_MARK(2);
     constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       conv2_phase<K, decltype(nb)::value * WR23>((g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s,
                                                  (l_bf16_p)y2s, nq, tid, wave);
     });
     __syncthreads();
-    PHASE_MARK(3);
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq,
                                                  (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, tid, wave);
@@ -811,7 +802,6 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch
   }
-  PHASE_MARK(4);
 }
 
 // Rewrites W1|W2|W3 in the order the fused kernel's waves consume them: one 16x32 MFMA
@@ -869,12 +859,17 @@ inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<u
 }
 
 template <class K>
+hipError_t prepare_one() {
+  static std::atomic<unsigned long long> lds_allowed{0};
+  return allow_dynamic_lds((const void*)fused_bneck_kernel<K>, K::LDS_BYTES, lds_allowed);
+}
+
+template <class K>
 hipError_t launch_one(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
                       const void* packed, const float* b1, const float* b2, const float* b3,
                       void* out, bool post_relu, hipStream_t st) {
   auto k = fused_bneck_kernel<K>;
-  static std::atomic<unsigned long long> lds_allowed{0};
-  if (hipError_t e = allow_dynamic_lds((const void*)k, K::LDS_BYTES, lds_allowed); e != hipSuccess) return e;
+  if (hipError_t e = prepare_one<K>(); e != hipSuccess) return e;
   const int slots = device_cu_count() * ((160 * 1024) / K::LDS_BYTES);
   int grid = (g.P + K::PPW - 1) / K::PPW;
   grid = (grid + slots - 1) / slots * slots;
@@ -890,7 +885,7 @@ hipError_t launch_one(const Geom& g, const void* x, const int32_t* idx, const in
 
 template <class K>
 constexpr MfmaVariant variant_of() {
-  return MfmaVariant{K::C, K::M, K::S, K::PACKED_ELEMS * 2, &pack_one<K>, &launch_one<K>};
+  return MfmaVariant{K::C, K::M, K::S, K::PACKED_ELEMS * 2, 0, &prepare_one<K>, &pack_one<K>, &launch_one<K>};
 }
 
 }  // namespace
@@ -903,13 +898,5 @@ constexpr MfmaVariant variant_of() {
     *n = (int)(sizeof(table) / sizeof(table[0]));                   \
     return table;                                                   \
   }
-#ifdef LASNET_PHASE_CLOCKS
-#define LASNET_DEFINE_CLOCK_READER(name)                                                            \
-  extern "C" __attribute__((visibility("default"))) int lasnet_debug_read_clocks_##name(long long* host, int n) { \
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase_clk), sizeof(long long) * n);         \
-  }
-#else
-#define LASNET_DEFINE_CLOCK_READER(name)
-#endif
 
 }  // namespace lasnet

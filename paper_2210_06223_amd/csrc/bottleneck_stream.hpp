@@ -109,8 +109,12 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
     const int cell = idx ? idx[tb + i] : tb + i;
     const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
     const int gy = rem / g.GW, gx = rem - gy * g.GW;
-    const int h0 = gy * S - 1, w0 = gx * S - 1;
-    hdr[i * 4 + 0] = (n * g.H + h0) * g.W + w0;
+    int h0 = gy * S - 1, w0 = gx * S - 1, base = (n * g.H + h0) * g.W + w0;
+    if ((unsigned)cell >= (unsigned)g.P) {                   // not a cell of this map: a window that lies
+      h0 = w0 = -(1 << 20);                                  // wholly outside the image (nothing is stored
+      base = -(g.W + 1);                                     // for it; its loads read pixel 0)
+    }
+    hdr[i * 4 + 0] = base;
     hdr[i * 4 + 1] = h0;
     hdr[i * 4 + 2] = w0;
   }
@@ -192,13 +196,6 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
   if (npat > 1) decode(1);
   __syncthreads();
   issue_x(0);
-#ifdef LASNET_PHASE_CLOCKS
-  long long clk_acc[4] = {0, 0, 0, 0}, clk_t = wall_clock64();   // time in: top wait, conv1, conv2, conv3
-  const long long clk_t0 = clk_t;
-#define STREAM_MARK(i) do { const long long now_ = wall_clock64(); clk_acc[i] += now_ - clk_t; clk_t = now_; } while (0)
-#else
-#define STREAM_MARK(i) do { } while (0)
-#endif
 
   for (int p = 0; p < npat; ++p) {
     AS_LDS const char* xc = xs + (p & 1) * (K::R1 * K::XROW);
@@ -208,7 +205,6 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
     // here measured the same.)
     barrier_keep_vm<0>();
     if (p + 1 < npat) issue_x(p + 1);
-    STREAM_MARK(0);
 
     // ------------------------------------------------------------------ conv1
     {
@@ -264,7 +260,6 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
       }
     }
     barrier_keep_vm<63>();                                 // LDS only: the next window stays in flight
-    STREAM_MARK(1);
     if (p + 2 < npat) decode(p + 2);                       // read after the next patch's first barrier
 
     // ------------------------------------------------------------------ conv2
@@ -325,7 +320,6 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
       }
     }
     barrier_keep_vm<63>();
-    STREAM_MARK(2);
 
     // ------------------------------------------------------------------ conv3 + residual + store
     {
@@ -397,34 +391,36 @@ __global__ __launch_bounds__(K::NT, 1) void stream_bneck_kernel(
             const int pr = half * 8 + (lane >> 3);
             const bf16x8 v = *reinterpret_cast<AS_LDS const bf16x8*>(tr + gg * 2048 + pr * 128 + ((c8l ^ (pr & 7)) << 4));
             const int qq = (wr + K::WR * i) * 16 + pr;
-            const int px = pix[(qq / S + 1) * T + qq % S + 1];   // own pixels are always inside the image
-            __builtin_nontemporal_store(v, reinterpret_cast<AS_GLOBAL bf16x8*>((AS_GLOBAL __bf16*)out + (size_t)px * C + chb + c8l * 8));
+            const int px = pix[(qq / S + 1) * T + qq % S + 1];   // own pixels are inside the image, unless the entry was invalid
+            if (px >= 0)
+              __builtin_nontemporal_store(v, reinterpret_cast<AS_GLOBAL bf16x8*>((AS_GLOBAL __bf16*)out + (size_t)px * C + chb + c8l * 8));
           }
         }
       }
     }
-    STREAM_MARK(3);
   }
-#ifdef LASNET_PHASE_CLOCKS
-  if (tid == 0 && blockIdx.x < 2048) {
-    long long t = clk_t0;
-    g_phase_clk[blockIdx.x * 6 + 0] = t;
-    for (int i = 0; i < 4; ++i) { t += clk_acc[i]; g_phase_clk[blockIdx.x * 6 + 1 + i] = t; }
-    g_phase_clk[blockIdx.x * 6 + 5] = npat;
-  }
-#endif
-#undef STREAM_MARK
 }
+
+template <class K>
+hipError_t prepare_stream() {
+  static std::atomic<unsigned long long> lds_allowed[2];
+  if (hipError_t e = allow_dynamic_lds((const void*)stream_bneck_kernel<K, false>, K::LDS_BYTES, lds_allowed[0]);
+      e != hipSuccess)
+    return e;
+  return allow_dynamic_lds((const void*)stream_bneck_kernel<K, true>, K::LDS_BYTES, lds_allowed[1]);
+}
+
+// Byte offsets from x are 32-bit inside the kernel.
+template <class K>
+constexpr size_t stream_max_map_bytes() { return (size_t)1 << 31; }
 
 template <class K>
 hipError_t launch_stream(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
                          const void* packed, const float* b1, const float* b2, const float* b3,
                          void* out, bool post_relu, hipStream_t st) {
-  if ((size_t)g.N * g.H * g.W * K::C * 2 > ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit offsets
+  if ((size_t)g.N * g.H * g.W * K::C * 2 > stream_max_map_bytes<K>()) return hipErrorInvalidValue;
   auto k = post_relu ? stream_bneck_kernel<K, true> : stream_bneck_kernel<K, false>;
-  static std::atomic<unsigned long long> lds_allowed[2];
-  if (hipError_t e = allow_dynamic_lds((const void*)k, K::LDS_BYTES, lds_allowed[post_relu]); e != hipSuccess)
-    return e;
+  if (hipError_t e = prepare_stream<K>(); e != hipSuccess) return e;
   // one persistent workgroup per CU; more only when a run would exceed what a workgroup stages
   int grid = device_cu_count();
   const int need = (g.P + K::MAXQ - 1) / K::MAXQ;

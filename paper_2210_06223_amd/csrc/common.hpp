@@ -45,6 +45,8 @@ hipError_t launch_generic(int dtype, const Geom& g, const void* x, const int32_t
 struct MfmaVariant {
   int C, M, S;
   size_t packed_bytes;
+  size_t max_map_bytes;      // largest feature map the kernel addresses (0 = no limit of its own)
+  hipError_t (*prepare)();   // host-side set-up that can fail (per-device kernel attributes); enqueues nothing
   hipError_t (*pack)(const void* W1, const void* W2, const void* W3, void* packed, hipStream_t st);
   hipError_t (*launch)(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
                        const void* packed, const float* b1, const float* b2, const float* b3,
@@ -55,6 +57,9 @@ int device_cu_count();
 // Matrix-core kernel: only for the (C, M, S) it was instantiated for.  It reads the three
 // weight tensors from one buffer of mfma_packed_bytes() that launch_pack() fills.
 bool mfma_supported(int C, int M, int S);
+size_t mfma_max_map_bytes(int C, int M, int S);
+hipError_t prepare_mfma(int C, int M, int S);
+hipError_t prepare_generic(int dtype);
 size_t mfma_packed_bytes(int C, int M, int S);
 hipError_t launch_pack(int C, int M, int S, const void* W1, const void* W2, const void* W3,
                        void* packed, hipStream_t st);

@@ -15,25 +15,17 @@ using K_s1s1 = Cfg<256, 64, 1, 16, 112, 4, 64, 4, 1, 4, 1, 4, 6, 1, 4, 4, 2>;   
 }  // namespace
 
 // S=8 runs on the streaming, weight-stationary kernel; it reads the buffer that K_s1's packing
-// writes.  Maps beyond its 32-bit byte offsets go to the fused kernel.
+// writes (K_s1 is instantiated for its packing only).  Maps beyond the kernel's 32-bit byte offsets
+// are left to the generic kernel by the dispatcher.
 using KS_s1 = StreamCfg<256, 64, 8>;
-namespace {
-hipError_t launch_s8(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
-                     const void* packed, const float* b1, const float* b2, const float* b3, void* out,
-                     bool post_relu, hipStream_t st) {
-  if ((size_t)g.N * g.H * g.W * KS_s1::C * 2 <= ((size_t)1 << 31))
-    return launch_stream<KS_s1>(g, x, idx, count, packed, b1, b2, b3, out, post_relu, st);
-  return launch_one<K_s1>(g, x, idx, count, packed, b1, b2, b3, out, post_relu, st);
-}
-}  // namespace
 
 #define LASNET_CFGS(X) X(K_s1s4) X(K_s1s7) X(K_s1s2) X(K_s1s1)
 const MfmaVariant* mfma_variants_stage1(int* n) {
   static const MfmaVariant table[] = {
-      MfmaVariant{K_s1::C, K_s1::M, K_s1::S, K_s1::PACKED_ELEMS * 2, &pack_one<K_s1>, &launch_s8},
+      MfmaVariant{K_s1::C, K_s1::M, K_s1::S, K_s1::PACKED_ELEMS * 2, stream_max_map_bytes<KS_s1>(),
+                  &prepare_stream<KS_s1>, &pack_one<K_s1>, &launch_stream<KS_s1>},
       LASNET_CFGS(LASNET_VARIANT_ENTRY)};
   *n = (int)(sizeof(table) / sizeof(table[0]));
   return table;
 }
 }  // namespace lasnet
-namespace lasnet { LASNET_DEFINE_CLOCK_READER(stage1) }

@@ -16,4 +16,3 @@ using K_s2s1 = Cfg<512, 128, 1, 24, 112, 4, 64, 3, 1, 4, 1, 4, 4, 1, 4, 4, 2>;  
 #define LASNET_CFGS(X) X(K_s2) X(K_s2s7) X(K_s2s2) X(K_s2s1)
 LASNET_DEFINE_VARIANT_TABLE(stage2, LASNET_CFGS)
 }  // namespace lasnet
-namespace lasnet { LASNET_DEFINE_CLOCK_READER(stage2) }

@@ -16,4 +16,3 @@ using K_s3s1 = Cfg<1024, 256, 1, 64, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>; 
 #define LASNET_CFGS(X) X(K_s3) X(K_s3s7) X(K_s3s1)
 LASNET_DEFINE_VARIANT_TABLE(stage3, LASNET_CFGS)
 }  // namespace lasnet
-namespace lasnet { LASNET_DEFINE_CLOCK_READER(stage3) }

@@ -12,4 +12,3 @@ using K_s4 = Cfg<2048, 512, 1, 16, 96, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    
 #define LASNET_CFGS(X) X(K_s4)
 LASNET_DEFINE_VARIANT_TABLE(stage4, LASNET_CFGS)
 }  // namespace lasnet
-namespace lasnet { LASNET_DEFINE_CLOCK_READER(stage4) }

@@ -377,3 +377,116 @@ def test_full_size_workloads_as_the_benchmark_launches_them(name):
     ref = O.sparse_bottleneck(inp.f64["x"], mask_o, cfg.S, *_oracle_w(inp))
     up = np.broadcast_to(O.upsample_mask(mask_o, cfg.S)[..., None], ref.shape)
     U.assert_block_close(out, ref, d["x"], up, cfg.dtype, cfg.name)
+
+
+# ------------------------------------------------------------------ batch 1, non-square maps, list hygiene
+def test_block_at_batch_one():
+    """One stage-3 image (49 cells): most workgroups get a single patch."""
+    cfg = synth.CONFIGS["stage3_b1"]
+    _run_case(cfg, k=24)
+    _run_case(cfg, k=25, flags=B.LASNET_POST_RELU)
+
+
+NONSQUARE_CASES = [
+    (synth.BlockConfig("s3_S2_6x10", 3, 6, 10, 1024, 256, 2, "bf16", 0.5, 51), 23),     # 45 cells
+    (synth.BlockConfig("s2_S4_8x12", 2, 8, 12, 512, 128, 4, "bf16", 0.5, 52), 7),       # 12 cells
+    (synth.BlockConfig("s4_S1_3x5", 5, 3, 5, 2048, 512, 1, "bf16", 0.5, 53), 37),       # 75 cells
+    (synth.BlockConfig("s1_S8_8x24", 2, 8, 24, 256, 64, 8, "bf16", 0.5, 54), 3),        # streaming kernel, 6 cells
+]
+
+
+@pytest.mark.parametrize("cfg,k", NONSQUARE_CASES, ids=lambda v: getattr(v, "name", str(v)))
+def test_mfma_kernels_on_non_square_maps(cfg, k):
+    assert B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, cfg.S) == 1
+    _run_case(cfg, k=k)
+    _run_case(cfg, k=cfg.P)
+
+
+@pytest.mark.parametrize("cfg", [_cfg("stage3_b128", N=2, name="s3_hyg"), _cfg("stage1_b64", N=1, name="s1_hyg"),
+                                 _cfg("tiny_f32")], ids=lambda c: c.name)
+def test_count_beyond_capacity_and_invalid_entries(cfg):
+    """count[0] > P is read as P; entries that are not cells of the map are ignored (the kernels
+    check them, so a bad list cannot send a load or store outside the buffers)."""
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    w = U.weights(d)
+    f, _, _ = O.residual_branch(inp.f64["x"], *_oracle_w(inp))
+    # (1) a full list with an overstated count == every cell active
+    idx = torch.arange(cfg.P, dtype=torch.int32, device="cuda")
+    count = torch.tensor([cfg.P + 5], dtype=torch.int32, device="cuda")
+    out = torch.full_like(d["x"], 777.0)
+    B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *w, out=out)
+    torch.cuda.synchronize()
+    ones = np.ones((cfg.N, cfg.G, cfg.GW), np.uint8)
+    ref = O.masked_output(inp.f64["x"], f, ones, cfg.S)
+    U.assert_block_close(out, ref, d["x"], np.ones(ref.shape, bool), cfg.dtype, cfg.name)
+    # (2) valid entries mixed with invalid ones, and a run of invalid ones long enough to fill a batch
+    good = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.4, seed=77)
+    bad = np.array([-1, cfg.P, cfg.P + 123, -2**31, 2**31 - 1] * 8, np.int32)
+    mixed = np.concatenate([bad[:3], good[: len(good) // 2], bad, good[len(good) // 2:], bad[:2]]).astype(np.int32)
+    mask = np.zeros(cfg.P, np.uint8); mask[good] = 1
+    mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
+    idx = torch.from_numpy(mixed).cuda()
+    count = torch.tensor([len(mixed)], dtype=torch.int32, device="cuda")
+    out = torch.full_like(d["x"], 777.0)
+    B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *w, out=out)
+    torch.cuda.synchronize()
+    ref = O.masked_output(inp.f64["x"], f, mask, cfg.S)
+    up = np.broadcast_to(O.upsample_mask(mask, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(out, ref, d["x"], up, cfg.dtype, cfg.name)
+
+
+# ------------------------------------------------------------------ ratio sweep at full size
+@pytest.mark.parametrize("name", ["stage2_b128", "stage3_b128", "stage4_b128"])
+def test_ratio_sweep_index_lists_at_full_size(name):
+    """The latency-against-ratio sweep as bench.py launches it (index lists with Beta-distributed
+    per-image ratios, iid cells and one blob per image, fed straight to the prepacked entry with the
+    identity pass-through skipped): every list against the oracle.  F(x) does not depend on the mask,
+    so the oracle computes it once."""
+    cfg = synth.CONFIGS[name]
+    _say("ratio sweep", cfg)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    f, _, _ = O.residual_branch(inp.f64["x"], *_oracle_w(inp))
+    packed = B.lasnet_pack_weights(cfg.S, d["W1"], d["W2"], d["W3"])
+    for r in (0.1, 0.25, 0.5, 0.75, 1.0):
+        for structure in ("iid", "blob"):
+            il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, r, seed=cfg.seed, structure=structure)
+            _say("  r", r, structure, len(il))
+            mask = np.zeros(cfg.P, np.uint8); mask[il] = 1
+            mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
+            idx = torch.zeros((cfg.P,), dtype=torch.int32, device="cuda")
+            idx[: len(il)] = torch.from_numpy(il).cuda()
+            count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
+            out = d["x"].clone()                                   # what the masker's pass-through leaves
+            B.lasnet_sparse_bottleneck_packed(d["x"], idx, count, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
+                                              out=out, flags=B.LASNET_SKIP_IDENTITY)
+            torch.cuda.synchronize()
+            ref = O.masked_output(inp.f64["x"], f, mask, cfg.S)
+            up = np.broadcast_to(O.upsample_mask(mask, cfg.S)[..., None], ref.shape)
+            U.assert_block_close(out, ref, d["x"], up, cfg.dtype, "%s r=%g %s" % (cfg.name, r, structure))
+
+
+# ------------------------------------------------------------------ the check build
+def test_check_build_with_drained_barriers_is_bit_identical(monkeypatch):
+    """The matrix-core kernels keep global->LDS loads in flight across barriers and wait for them with
+    counts worked out by hand from the program order of each wave's memory operations.  The check build
+    of the same sources waits for everything at those barriers.  If a count were off (say after a
+    compiler moved a load), the production build would read stale LDS and differ from it."""
+    from paper_2210_06223_amd import build as _build
+    alt = B.load_library(_build.LIB_CHECK)
+    assert alt is not B.lib()
+    for cfg, k in MFMA_CASES + NONSQUARE_CASES:
+        _say("check build", cfg.name)
+        inp = synth.make_block_inputs(cfg)
+        d = U.dev_inputs(inp)
+        il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, k / cfg.P, seed=cfg.seed + 1000)
+        idx = torch.from_numpy(il).cuda() if len(il) else torch.zeros(1, dtype=torch.int32, device="cuda")
+        count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
+        outs = []
+        for L in (B.lib(), alt):
+            monkeypatch.setattr(B, "_lib", L)
+            outs.append(B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d)))
+            torch.cuda.synchronize()
+        monkeypatch.undo()
+        assert np.array_equal(U.bits(outs[0]), U.bits(outs[1])), cfg.name
