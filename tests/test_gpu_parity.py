@@ -422,8 +422,10 @@ def test_count_beyond_capacity_and_invalid_entries(cfg):
     U.assert_block_close(out, ref, d["x"], np.ones(ref.shape, bool), cfg.dtype, cfg.name)
     # (2) valid entries mixed with invalid ones, and a run of invalid ones long enough to fill a batch
     good = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.4, seed=77)
-    bad = np.array([-1, cfg.P, cfg.P + 123, -2**31, 2**31 - 1] * 8, np.int32)
+    room = cfg.P - len(good)                                   # the list's capacity is P entries
+    bad = np.array([-1, cfg.P, cfg.P + 123, -2**31, 2**31 - 1] * 8, np.int32)[: max(0, room - 5)]
     mixed = np.concatenate([bad[:3], good[: len(good) // 2], bad, good[len(good) // 2:], bad[:2]]).astype(np.int32)
+    assert len(good) < len(mixed) <= cfg.P
     mask = np.zeros(cfg.P, np.uint8); mask[good] = 1
     mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
     idx = torch.from_numpy(mixed).cuda()
