@@ -49,7 +49,9 @@ typedef enum {
   LASNET_ESHAPE = -2,       /* S does not divide H or W; out shape/dtype differs from x  */
   LASNET_EUNSUPPORTED = -3, /* shape outside what the kernels were built for             */
   LASNET_EALIAS = -4,       /* out aliases x (see lasnet_sparse_bottleneck)              */
-  LASNET_EHIP = -5          /* HIP runtime error (no device, launch failure)             */
+  LASNET_EHIP = -5,         /* HIP runtime error (no device, launch failure)             */
+  LASNET_ETOOBIG = -6       /* lasnet_sparse_bottleneck_noalloc: the shape's repacked weights
+                               exceed LASNET_NOALLOC_MAX_PACKED_BYTES                     */
 } lasnet_status;
 
 typedef enum { LASNET_F32 = 0, LASNET_BF16 = 1 } lasnet_dtype;
@@ -176,6 +178,31 @@ LASNET_API int lasnet_sparse_bottleneck_packed(const lasnet_tensor* x, const int
                                                const float* b2, const float* b3,
                                                lasnet_tensor* out, uint32_t flags,
                                                void* hip_stream);
+
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): lasnet_sparse_bottleneck_ex with the per-call weight
+ * repack going to a fixed array in device memory instead of the library's per-stream buffer.
+ * This entry point calls no hipMalloc / hipFree and no allocating library routine, on any call.
+ *   - The array is LASNET_NOALLOC_MAX_PACKED_BYTES long, exists once per GPU the library runs
+ *     on, and is held until the process ends.  Shapes whose repacked weights
+ *     (lasnet_packed_weights_bytes) are larger -- the 7x7 stage of ResNet-101, 8.5 MiB -- get
+ *     LASNET_ETOOBIG before anything is enqueued; such callers repack once into a buffer of their
+ *     own and use lasnet_sparse_bottleneck_packed, which allocates nothing either.
+ *   - All calls on one GPU share the array (each call rewrites the part it uses before reading
+ *     it, so nothing has to be cleared between calls): calls that overlap on one GPU -- different
+ *     streams, or host threads on different streams -- race on it.  Calls on one stream are
+ *     ordered and safe.
+ *   - Shapes without a matrix-core kernel run the generic kernel, which needs no scratch.
+ * Arguments, semantics, flags and results are those of lasnet_sparse_bottleneck_ex, bit for bit.
+ */
+#define LASNET_NOALLOC_MAX_PACKED_BYTES (4u << 20)
+LASNET_API int lasnet_sparse_bottleneck_noalloc(const lasnet_tensor* x, const int32_t* idx,
+                                                const int32_t* count, int S, int M,
+                                                const void* W1, const float* b1,
+                                                const void* W2, const float* b2,
+                                                const void* W3, const float* b3,
+                                                lasnet_tensor* out, uint32_t flags, void* hip_stream);
 
 /*
  * The static block (activation rate 1, no masker): out = x + F(x) at every pixel -- the

@@ -19,12 +19,14 @@ _lib = None
 LASNET_F32, LASNET_BF16 = 0, 1
 LASNET_POST_RELU, LASNET_FORCE_GENERIC, LASNET_SKIP_IDENTITY = 1, 2, 4
 LASNET_OK, LASNET_EINVAL, LASNET_ESHAPE, LASNET_EUNSUPPORTED, LASNET_EALIAS, LASNET_EHIP = 0, -1, -2, -3, -4, -5
+LASNET_ETOOBIG = -6
+LASNET_NOALLOC_MAX_PACKED_BYTES = 4 << 20
 
 EXPORTS = (
     "lasnet_version", "lasnet_status_string", "lasnet_masker", "lasnet_masker_ex", "lasnet_masker_logits",
     "lasnet_sparse_bottleneck", "lasnet_sparse_bottleneck_ex", "lasnet_dense_bottleneck",
     "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
-    "lasnet_sparse_bottleneck_packed",
+    "lasnet_sparse_bottleneck_packed", "lasnet_sparse_bottleneck_noalloc",
 )
 
 
@@ -63,6 +65,8 @@ def load_library(path: str) -> ctypes.CDLL:
     L.lasnet_sparse_bottleneck_ex.restype = ip
     L.lasnet_sparse_bottleneck_ex.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp,
                                               ctypes.c_uint32, vp]
+    L.lasnet_sparse_bottleneck_noalloc.restype = ip
+    L.lasnet_sparse_bottleneck_noalloc.argtypes = L.lasnet_sparse_bottleneck_ex.argtypes
     L.lasnet_dense_bottleneck.restype = ip
     L.lasnet_dense_bottleneck.argtypes = [tp, ip, vp, vp, vp, vp, vp, vp, tp, ctypes.c_uint32, vp]
     L.lasnet_has_fast_path.restype = ip
@@ -222,6 +226,23 @@ def lasnet_sparse_bottleneck(x: torch.Tensor, idx: Optional[torch.Tensor],
         st = lib().lasnet_sparse_bottleneck(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), M, *w,
                                             ctypes.byref(o), _stream(stream))
     _check(st, "lasnet_sparse_bottleneck")
+    return out
+
+
+def lasnet_sparse_bottleneck_noalloc(x: torch.Tensor, idx: Optional[torch.Tensor],
+                                     count: Optional[torch.Tensor], S: int, W1, b1, W2, b2, W3, b3,
+                                     out: torch.Tensor, flags: int = 0, stream=None) -> torch.Tensor:
+    """lasnet_sparse_bottleneck_ex whose weight repack goes to the library's fixed scratch array; `out` is
+    the caller's (this wrapper allocates nothing either)."""
+    d = _as_tensor_desc(x)
+    o = _as_tensor_desc(out)
+    M, w = _weights(x, W1, b1, W2, b2, W3, b3)
+    for n, t in (("idx", idx), ("count", count)):
+        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    st = lib().lasnet_sparse_bottleneck_noalloc(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), M, *w,
+                                                ctypes.byref(o), int(flags), _stream(stream))
+    _check(st, "lasnet_sparse_bottleneck_noalloc")
     return out
 
 

@@ -36,6 +36,33 @@ void* get_workspace(hipStream_t st, size_t bytes) {
   return w.ptr;
 }
 
+// Repacked weights for callers that cannot allocate (lasnet_sparse_bottleneck_noalloc): a fixed
+// array in device memory, one copy per GPU the library runs on, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the address that
+// kernels and copies take is the one that call returns, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[LASNET_NOALLOC_MAX_PACKED_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];                // per device; nullptr = not looked up yet
+std::mutex g_scratch_mu;
+
+void* scratch_for_current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
 bool device_ok() {
   int n = 0;
   if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
@@ -66,12 +93,12 @@ int dense_tile(int dtype, int H, int W, int C, int M, bool force_generic) {
   return 0;
 }
 
-// packed != nullptr: the caller passes repacked weights (W1..W3 unused).  scratch != nullptr: raw weights
-// are repacked into that buffer of scratch_bytes instead of the library's per-stream one.
+// packed != nullptr: the caller passes repacked weights (W1..W3 unused).  use_scratch: raw weights are
+// repacked into this device's `scratch` array instead of the library's per-stream buffer (no allocation).
 int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S, int M,
               const void* W1, const float* b1, const void* W2, const float* b2, const void* W3,
               const float* b3, const void* packed, lasnet_tensor* out, uint32_t flags, bool dense,
-              void* stream, void* scratch = nullptr, size_t scratch_bytes = 0) {
+              void* stream, bool use_scratch = false) {
   int s = check_tensor(x);
   if (s != LASNET_OK) return s;
   if (!out) return LASNET_EINVAL;
@@ -105,6 +132,8 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   }
   if (packed && !fast) return LASNET_EUNSUPPORTED;
   if (!fast && !generic_fits(M, S)) return LASNET_EUNSUPPORTED;
+  if (fast && !packed && use_scratch && mfma_packed_bytes(x->c, M, S) > sizeof(scratch))
+    return LASNET_ETOOBIG;
   if (!device_ok()) return LASNET_EHIP;
   if (x->n == 0) return LASNET_OK;
 
@@ -119,14 +148,8 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   if (e != hipSuccess) return LASNET_EHIP;
   if (fast && !packed) {
     const size_t need = mfma_packed_bytes(x->c, M, S);
-    void* ws = nullptr;
-    if (scratch) {
-      if (need > scratch_bytes) return LASNET_EUNSUPPORTED;
-      ws = scratch;
-    } else {
-      ws = get_workspace(st, need);
-      if (!ws) return LASNET_EHIP;
-    }
+    void* ws = use_scratch ? scratch_for_current_device() : get_workspace(st, need);
+    if (!ws) return LASNET_EHIP;
     e = launch_pack(x->c, M, S, W1, W2, W3, ws, st);
     if (e != hipSuccess) return LASNET_EHIP;
     packed = ws;
@@ -179,6 +202,7 @@ const char* lasnet_status_string(int status) {
     case LASNET_EUNSUPPORTED: return "shape not supported by the built kernels";
     case LASNET_EALIAS: return "out must not alias x";
     case LASNET_EHIP: return "HIP runtime error or no gfx950 device";
+    case LASNET_ETOOBIG: return "repacked weights exceed the fixed scratch array of lasnet_sparse_bottleneck_noalloc";
     default: return "unknown status";
   }
 }
@@ -242,6 +266,14 @@ int lasnet_sparse_bottleneck(const lasnet_tensor* x, const int32_t* idx, const i
                              const float* b2, const void* W3, const float* b3, lasnet_tensor* out,
                              void* hip_stream) {
   return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, nullptr, out, 0u, false, hip_stream);
+}
+
+int lasnet_sparse_bottleneck_noalloc(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                                     int S, int M, const void* W1, const float* b1, const void* W2,
+                                     const float* b2, const void* W3, const float* b3,
+                                     lasnet_tensor* out, uint32_t flags, void* hip_stream) {
+  return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, nullptr, out, flags, false,
+                   hip_stream, /*use_scratch=*/true);
 }
 
 int lasnet_dense_bottleneck(const lasnet_tensor* x, int M, const void* W1, const float* b1,
