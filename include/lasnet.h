@@ -68,8 +68,13 @@ enum {
   LASNET_POST_RELU = 1,        /* ReLU after the residual add, on active patches only       */
   LASNET_FORCE_GENERIC = 2,    /* use the shape-generic scalar-FMA kernel (fp32 accumulate,
                                   no intermediate rounding) even where an MFMA kernel exists */
-  LASNET_SKIP_IDENTITY = 4     /* caller guarantees out already equals x on inactive patches:
+  LASNET_SKIP_IDENTITY = 4,    /* caller guarantees out already equals x on inactive patches:
                                   do not copy x to out first                                 */
+  LASNET_FORCE_FUSED = 8,      /* run the one-kernel (fused) schedule even where the library would
+                                  pick the tiled one (see "Schedules" below); for measurements  */
+  LASNET_FORCE_TILED = 16      /* run the three-kernel (tiled) schedule where the shape has one but
+                                  the library would pick the fused one; LASNET_EUNSUPPORTED where
+                                  it has none, or in lasnet_sparse_bottleneck_noalloc           */
 };
 
 LASNET_API int lasnet_version(void);
@@ -149,6 +154,27 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
                                 lasnet_tensor* out, uint32_t flags, void* hip_stream);
 
 /*
+ * Schedules.  Two matrix-core schedules exist, and the library picks by shape (Sec. 3.4 discusses
+ * this choice of operator fusion against the activation rate; on this GPU the block shape decides):
+ *   fused  one kernel: gather + conv1 + conv3x3 + conv3 + scatter-add, y1 and y2 never leave the CU.
+ *          Used where the weights are small against the maps (ResNet-101 stages 1-2).
+ *   tiled  the paper's own operator split (Sec. 3.4, App. B.1): conv1 over the pixels that some
+ *          active patch needs | gather + conv3x3 | conv3 + scatter-add, as three kernels with y1 and
+ *          y2 passing through a workspace in device memory.  Built for 1024x256 channels on maps of
+ *          up to 196 pixels (14x14) and 2048x512 channels on maps of up to 49 pixels (7x7), any patch
+ *          size.  The library's own choice for 2048x512 (measured faster there at every activation
+ *          rate); for 1024x256 the fused kernel measured faster at every rate, so the tiled one
+ *          runs only with LASNET_FORCE_TILED.
+ * Results are the same function of the inputs either way (same roundings: y1, y2 to bf16, out once).
+ * The tiled schedule needs lasnet_workspace_bytes() of device memory (that query answers for every
+ * shape that has a tiled schedule, chosen by default or not; 0 = none): lasnet_sparse_bottleneck[_ex],
+ * lasnet_dense_bottleneck and lasnet_sparse_bottleneck_packed take it from the library's per-stream
+ * buffer (see below); lasnet_sparse_bottleneck_planned takes it from the caller;
+ * lasnet_sparse_bottleneck_noalloc never uses the tiled schedule.
+ */
+LASNET_API size_t lasnet_workspace_bytes(int dtype, int N, int H, int W, int C, int M, int S);
+
+/*
  * Weight repacking for the matrix-core kernels.  Those kernels read W1, W2, W3 from ONE
  * buffer in which the weights are laid out fragment by fragment in the order the waves
  * consume them.  lasnet_sparse_bottleneck[_ex] and lasnet_dense_bottleneck take the plain
@@ -165,9 +191,18 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
  *                                                         matrix-core kernel
  *   lasnet_pack_weights(..., packed, stream)              packed: caller's device buffer
  * The layout depends on (C, M, S); a packed buffer is only valid for the shape it was
- * made for.  lasnet_sparse_bottleneck_packed is otherwise lasnet_sparse_bottleneck_ex
- * (same semantics, flags LASNET_POST_RELU and LASNET_SKIP_IDENTITY) and returns
- * LASNET_EUNSUPPORTED for shapes or dtypes without a matrix-core kernel.
+ * made for (both schedules read the same layout).  lasnet_sparse_bottleneck_packed is otherwise
+ * lasnet_sparse_bottleneck_ex (same semantics, flags LASNET_POST_RELU, LASNET_SKIP_IDENTITY and
+ * LASNET_FORCE_FUSED) and returns LASNET_EUNSUPPORTED for shapes or dtypes without a matrix-core
+ * kernel.  It allocates nothing on the fused schedule; on the tiled schedule the workspace comes
+ * from the library's per-stream buffer (hipMalloc on first use or growth, as above).
+ *
+ * lasnet_sparse_bottleneck_planned is the fully explicit form, which never allocates: packed
+ * weights AND the workspace are the caller's (workspace: 256-byte aligned device memory of at least
+ * lasnet_workspace_bytes(); may be NULL when that is 0; LASNET_EINVAL if too small), owned by the
+ * call until its work on the stream has finished.  mask: NULL, or the byte mask that lasnet_masker
+ * wrote for the same index list (mask[cell] != 0 exactly for the cells in idx[0 .. count[0])); the
+ * tiled schedule then reads it instead of scanning the list.
  */
 LASNET_API size_t lasnet_packed_weights_bytes(int dtype, int C, int M, int S);
 LASNET_API int lasnet_pack_weights(int dtype, int C, int M, int S, const void* W1, const void* W2,
@@ -178,6 +213,13 @@ LASNET_API int lasnet_sparse_bottleneck_packed(const lasnet_tensor* x, const int
                                                const float* b2, const float* b3,
                                                lasnet_tensor* out, uint32_t flags,
                                                void* hip_stream);
+LASNET_API int lasnet_sparse_bottleneck_planned(const lasnet_tensor* x, const int32_t* idx,
+                                                const int32_t* count, const uint8_t* mask,
+                                                int S, int M, const void* packed,
+                                                const float* b1, const float* b2, const float* b3,
+                                                lasnet_tensor* out, uint32_t flags,
+                                                void* workspace, size_t workspace_bytes,
+                                                void* hip_stream);
 
 /*
  * For callers that cannot allocate device memory (code under HIP graph capture, tight serving

@@ -17,7 +17,7 @@ _LIB_PATH = os.environ.get("LASNET_LIBRARY") or os.path.join(
 _lib = None
 
 LASNET_F32, LASNET_BF16 = 0, 1
-LASNET_POST_RELU, LASNET_FORCE_GENERIC, LASNET_SKIP_IDENTITY = 1, 2, 4
+LASNET_POST_RELU, LASNET_FORCE_GENERIC, LASNET_SKIP_IDENTITY, LASNET_FORCE_FUSED, LASNET_FORCE_TILED = 1, 2, 4, 8, 16
 LASNET_OK, LASNET_EINVAL, LASNET_ESHAPE, LASNET_EUNSUPPORTED, LASNET_EALIAS, LASNET_EHIP = 0, -1, -2, -3, -4, -5
 LASNET_ETOOBIG = -6
 LASNET_NOALLOC_MAX_PACKED_BYTES = 4 << 20
@@ -27,6 +27,7 @@ EXPORTS = (
     "lasnet_sparse_bottleneck", "lasnet_sparse_bottleneck_ex", "lasnet_dense_bottleneck",
     "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
     "lasnet_sparse_bottleneck_packed", "lasnet_sparse_bottleneck_noalloc",
+    "lasnet_workspace_bytes", "lasnet_sparse_bottleneck_planned",
 )
 
 
@@ -65,6 +66,11 @@ def load_library(path: str) -> ctypes.CDLL:
     L.lasnet_sparse_bottleneck_ex.restype = ip
     L.lasnet_sparse_bottleneck_ex.argtypes = [tp, vp, vp, ip, ip, vp, vp, vp, vp, vp, vp, tp,
                                               ctypes.c_uint32, vp]
+    L.lasnet_workspace_bytes.restype = ctypes.c_size_t
+    L.lasnet_workspace_bytes.argtypes = [ip] * 7
+    L.lasnet_sparse_bottleneck_planned.restype = ip
+    L.lasnet_sparse_bottleneck_planned.argtypes = [tp, vp, vp, vp, ip, ip, vp, vp, vp, vp, tp, ctypes.c_uint32,
+                                                   vp, ctypes.c_size_t, vp]
     L.lasnet_sparse_bottleneck_noalloc.restype = ip
     L.lasnet_sparse_bottleneck_noalloc.argtypes = L.lasnet_sparse_bottleneck_ex.argtypes
     L.lasnet_dense_bottleneck.restype = ip
@@ -226,6 +232,36 @@ def lasnet_sparse_bottleneck(x: torch.Tensor, idx: Optional[torch.Tensor],
         st = lib().lasnet_sparse_bottleneck(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), M, *w,
                                             ctypes.byref(o), _stream(stream))
     _check(st, "lasnet_sparse_bottleneck")
+    return out
+
+
+def lasnet_workspace_bytes(x: torch.Tensor, M: int, S: int) -> int:
+    """Device memory the tiled schedule needs for a call on x (0: the fused schedule runs, or no fast path)."""
+    n, h, w, c = x.shape
+    return int(lib().lasnet_workspace_bytes(LASNET_BF16 if x.dtype == torch.bfloat16 else LASNET_F32,
+                                            int(n), int(h), int(w), int(c), int(M), int(S)))
+
+
+def lasnet_sparse_bottleneck_planned(x: torch.Tensor, idx: Optional[torch.Tensor],
+                                     count: Optional[torch.Tensor], mask: Optional[torch.Tensor], S: int, M: int,
+                                     packed: torch.Tensor, b1, b2, b3, out: torch.Tensor,
+                                     workspace: Optional[torch.Tensor], flags: int = 0, stream=None) -> torch.Tensor:
+    """The explicit form: packed weights, workspace (a uint8 device tensor or None) and out are the caller's."""
+    d = _as_tensor_desc(x)
+    o = _as_tensor_desc(out)
+    for n, t in (("idx", idx), ("count", count)):
+        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    if mask is not None and (mask.dtype != torch.uint8 or not mask.is_cuda or not mask.is_contiguous()):
+        raise ValueError("mask must be a contiguous uint8 device tensor")
+    if b1.numel() != M or b2.numel() != M or b3.numel() != x.shape[3]:
+        raise ValueError("biases: b1 [M], b2 [M], b3 [C]")
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().lasnet_sparse_bottleneck_planned(ctypes.byref(d), _ptr(idx), _ptr(count), _ptr(mask), int(S), int(M),
+                                                _ptr(packed), _ptr(_f32(b1, "b1")), _ptr(_f32(b2, "b2")),
+                                                _ptr(_f32(b3, "b3")), ctypes.byref(o), int(flags),
+                                                _ptr(workspace), wbytes, _stream(stream))
+    _check(st, "lasnet_sparse_bottleneck_planned")
     return out
 
 

@@ -15,7 +15,7 @@ LIB = os.path.join(PKG, "liblasnet.so")
 # for all outstanding memory operations.  Only the tests load it (to compare the two bit for bit).
 LIB_CHECK = os.path.join(PKG, "liblasnet_check.so")
 CHECK_FLAGS = ("-DLASNET_DRAIN_AT_BARRIERS",)
-SOURCES = ["mfma_stage3.hip", "mfma_stage2.hip", "mfma_stage1.hip", "mfma_stage4.hip",   # slowest first
+SOURCES = ["tiled_stages.hip", "mfma_stage3.hip", "mfma_stage2.hip", "mfma_stage1.hip", "mfma_stage4.hip",   # slowest first
            "api.hip", "masker.hip", "bottleneck_generic.hip", "bottleneck_mfma.hip"]
 
 FLAGS = [
@@ -26,6 +26,12 @@ FLAGS = [
 ]
 
 
+# The k-loops of the matrix-core kernels must be unrolled in full (their register rings are indexed
+# by the loop counter; a ring that is not unrolled lands in scratch memory).  The long reductions of
+# the tiled kernels exceed the compiler's default size limit for `#pragma unroll`.
+PER_FILE_FLAGS = {"tiled_stages.hip": ["-mllvm", "-pragma-unroll-threshold=1048576"]}
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):
@@ -34,7 +40,7 @@ def hipcc() -> str:
 
 
 def _compile(cc, src, obj, extra_flags, verbose):
-    cmd = [cc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [cc, *FLAGS, *PER_FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

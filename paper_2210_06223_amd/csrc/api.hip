@@ -93,12 +93,29 @@ int dense_tile(int dtype, int H, int W, int C, int M, bool force_generic) {
   return 0;
 }
 
-// packed != nullptr: the caller passes repacked weights (W1..W3 unused).  use_scratch: raw weights are
-// repacked into this device's `scratch` array instead of the library's per-stream buffer (no allocation).
+// How a block call gets the device memory it needs beyond its arguments.
+struct Scratchpad {
+  bool fixed_array = false;        // raw weights are repacked into this device's `scratch` array (no allocation)
+  bool from_caller = false;        // `workspace` / `workspace_bytes` are the caller's
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+  const uint8_t* cellmask = nullptr;   // the masker's byte mask of the same list, if the caller passes it
+};
+
+Geom make_geom(const lasnet_tensor* x, int M, int S) {
+  Geom g;
+  g.N = x->n; g.H = x->h; g.W = x->w; g.C = x->c; g.M = M; g.S = S;
+  g.G = x->h / S; g.GW = x->w / S; g.P = x->n * g.G * g.GW;
+  return g;
+}
+
+size_t round256(size_t v) { return (v + 255) / 256 * 256; }
+
+// packed != nullptr: the caller passes repacked weights (W1..W3 unused).
 int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S, int M,
               const void* W1, const float* b1, const void* W2, const float* b2, const void* W3,
               const float* b3, const void* packed, lasnet_tensor* out, uint32_t flags, bool dense,
-              void* stream, bool use_scratch = false) {
+              void* stream, const Scratchpad& pad = Scratchpad()) {
   int s = check_tensor(x);
   if (s != LASNET_OK) return s;
   if (!out) return LASNET_EINVAL;
@@ -132,34 +149,61 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   }
   if (packed && !fast) return LASNET_EUNSUPPORTED;
   if (!fast && !generic_fits(M, S)) return LASNET_EUNSUPPORTED;
-  if (fast && !packed && use_scratch && mfma_packed_bytes(x->c, M, S) > sizeof(scratch))
+  if (fast && !packed && pad.fixed_array && mfma_packed_bytes(x->c, M, S) > sizeof(scratch))
     return LASNET_ETOOBIG;
+  const Geom g = make_geom(x, M, S);
+  // Deep stages run the tiled schedule (three kernels, y1 and y2 through a workspace) unless the
+  // caller asks for the fused kernel or cannot give or allow a workspace.
+  const TiledVariant* tiled = nullptr;
+  if (fast && !(flags & LASNET_FORCE_FUSED) && !pad.fixed_array) {
+    tiled = find_tiled(g);
+    if (tiled && !tiled->preferred && !(flags & LASNET_FORCE_TILED)) tiled = nullptr;
+  }
+  if ((flags & LASNET_FORCE_TILED) && !tiled) return LASNET_EUNSUPPORTED;
+  const size_t packed_need = (fast && !packed) ? round256(mfma_packed_bytes(x->c, M, S)) : 0;
+  const size_t tiled_need = tiled ? tiled->workspace_bytes(g) : 0;
+  if (pad.from_caller && tiled && (!pad.workspace || pad.workspace_bytes < tiled_need || ((uintptr_t)pad.workspace & 255)))
+    return LASNET_EINVAL;
   if (!device_ok()) return LASNET_EHIP;
   if (x->n == 0) return LASNET_OK;
 
-  Geom g;
-  g.N = x->n; g.H = x->h; g.W = x->w; g.C = x->c; g.M = M; g.S = S;
-  g.G = x->h / S; g.GW = x->w / S; g.P = x->n * g.G * g.GW;
   const BlockWeights w{W1, b1, W2, b2, W3, b3};
   hipStream_t st = (hipStream_t)stream;
   // Everything that can fail on the host comes before the first launch: kernel attributes, then the
-  // buffer for the repacked weights (the caller's, the library's per stream, or `scratch`).
-  hipError_t e = fast ? prepare_mfma(x->c, M, S) : prepare_generic(x->dtype);
+  // memory for the repacked weights and the tiled schedule's intermediates (the caller's, the
+  // library's per stream, or `scratch`).
+  hipError_t e = !fast ? prepare_generic(x->dtype) : tiled ? tiled->prepare() : prepare_mfma(x->c, M, S);
   if (e != hipSuccess) return LASNET_EHIP;
-  if (fast && !packed) {
-    const size_t need = mfma_packed_bytes(x->c, M, S);
-    void* ws = use_scratch ? scratch_for_current_device() : get_workspace(st, need);
+  unsigned char* tiled_ws = nullptr;
+  if (pad.from_caller) {
+    tiled_ws = (unsigned char*)pad.workspace;              // (this entry takes packed weights: packed_need is 0)
+  } else if (pad.fixed_array) {
+    if (packed_need) {
+      void* p = scratch_for_current_device();
+      if (!p) return LASNET_EHIP;
+      e = launch_pack(x->c, M, S, W1, W2, W3, p, st);
+      if (e != hipSuccess) return LASNET_EHIP;
+      packed = p;
+    }
+  } else if (packed_need + tiled_need) {
+    unsigned char* ws = (unsigned char*)get_workspace(st, packed_need + tiled_need);
     if (!ws) return LASNET_EHIP;
-    e = launch_pack(x->c, M, S, W1, W2, W3, ws, st);
-    if (e != hipSuccess) return LASNET_EHIP;
-    packed = ws;
+    if (packed_need) {
+      e = launch_pack(x->c, M, S, W1, W2, W3, ws, st);
+      if (e != hipSuccess) return LASNET_EHIP;
+      packed = ws;
+    }
+    tiled_ws = ws + packed_need;
   }
   if (!dense && idx && !(flags & LASNET_SKIP_IDENTITY)) {
     e = launch_copy(x->data, out->data, map_bytes, st);
     if (e != hipSuccess) return LASNET_EHIP;
   }
   const bool relu = (flags & LASNET_POST_RELU) != 0;
-  if (fast)
+  if (tiled)
+    e = tiled->launch(g, x->data, idx, count, idx ? pad.cellmask : nullptr, packed, b1, b2, b3, out->data, relu,
+                      tiled_ws, st);
+  else if (fast)
     e = launch_mfma(g, x->data, idx, count, packed, b1, b2, b3, out->data, relu, st);
   else
     e = launch_generic(x->dtype, g, x->data, idx, count, w, out->data, relu, st);
@@ -261,6 +305,30 @@ int lasnet_sparse_bottleneck_packed(const lasnet_tensor* x, const int32_t* idx, 
                    flags & ~(uint32_t)LASNET_FORCE_GENERIC, false, hip_stream);
 }
 
+size_t lasnet_workspace_bytes(int dtype, int N, int H, int W, int C, int M, int S) {
+  if (dtype != LASNET_BF16 || N <= 0 || H <= 0 || W <= 0 || C <= 0 || M <= 0 || S <= 0 || H % S || W % S) return 0;
+  if (!mfma_supported(C, M, S)) return 0;
+  lasnet_tensor t{nullptr, N, H, W, C, dtype};
+  const Geom g = make_geom(&t, M, S);
+  const TiledVariant* tv = find_tiled(g);
+  return tv ? tv->workspace_bytes(g) : 0;
+}
+
+int lasnet_sparse_bottleneck_planned(const lasnet_tensor* x, const int32_t* idx, const int32_t* count,
+                                     const uint8_t* mask, int S, int M, const void* packed,
+                                     const float* b1, const float* b2, const float* b3,
+                                     lasnet_tensor* out, uint32_t flags, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  if (!packed) return LASNET_EINVAL;
+  Scratchpad pad;
+  pad.from_caller = true;
+  pad.workspace = workspace;
+  pad.workspace_bytes = workspace_bytes;
+  pad.cellmask = mask;
+  return run_block(x, idx, count, S, M, nullptr, b1, nullptr, b2, nullptr, b3, packed, out,
+                   flags & ~(uint32_t)LASNET_FORCE_GENERIC, false, hip_stream, pad);
+}
+
 int lasnet_sparse_bottleneck(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, int S,
                              int M, const void* W1, const float* b1, const void* W2,
                              const float* b2, const void* W3, const float* b3, lasnet_tensor* out,
@@ -272,15 +340,18 @@ int lasnet_sparse_bottleneck_noalloc(const lasnet_tensor* x, const int32_t* idx,
                                      int S, int M, const void* W1, const float* b1, const void* W2,
                                      const float* b2, const void* W3, const float* b3,
                                      lasnet_tensor* out, uint32_t flags, void* hip_stream) {
+  Scratchpad fixed;
+  fixed.fixed_array = true;
   return run_block(x, idx, count, S, M, W1, b1, W2, b2, W3, b3, nullptr, out, flags, false,
-                   hip_stream, /*use_scratch=*/true);
+                   hip_stream, fixed);
 }
 
 int lasnet_dense_bottleneck(const lasnet_tensor* x, int M, const void* W1, const float* b1,
                             const void* W2, const float* b2, const void* W3, const float* b3,
                             lasnet_tensor* out, uint32_t flags, void* hip_stream) {
   return run_block(x, nullptr, nullptr, 0, M, W1, b1, W2, b2, W3, b3, nullptr, out,
-                   flags & (LASNET_POST_RELU | LASNET_FORCE_GENERIC), true, hip_stream);
+                   flags & (LASNET_POST_RELU | LASNET_FORCE_GENERIC | LASNET_FORCE_FUSED | LASNET_FORCE_TILED), true,
+                   hip_stream);
 }
 
 int lasnet_has_fast_path(int dtype, int C, int M, int S) {

@@ -22,6 +22,16 @@ const MfmaVariant* find_variant(int C, int M, int S) {
 }
 }  // namespace
 
+const TiledVariant* tiled_variants(int* n);
+
+const TiledVariant* find_tiled(const Geom& g) {
+  int n = 0;
+  const TiledVariant* t = tiled_variants(&n);
+  for (int i = 0; i < n; ++i)
+    if (t[i].C == g.C && t[i].M == g.M && t[i].takes(g)) return &t[i];
+  return nullptr;
+}
+
 int device_cu_count() {
   static std::atomic<int> cached[64];         // per device; 0 = not asked yet
   int dev = 0, n = 0;

@@ -66,6 +66,14 @@ struct Cfg {
   static constexpr int XMASK = KC / 8 - 1;
   static constexpr int YMASK = LDY / 8 - 1 < 15 ? LDY / 8 - 1 : 15;   // swizzle key bits of a y1/y2 row
   static constexpr int MS = M / 32;                    // k-steps over the mid channels
+  static constexpr int LDY2 = LDY, YMASK2 = YMASK;     // pitch / key bits of the y2 rows conv2 writes
+  // the packed weight buffers: bytes from one k-step's fragments to the next, and sizes
+  static constexpr int WD = 2;                         // conv1's weight ring, in chunks
+  static constexpr bool Y1_IN_XS = false;              // y1s is a region of its own
+  static constexpr bool ACTS_BARRIER = false;          // conv2 / conv3 find their LDS inputs complete on entry
+  static constexpr bool Y1_TO_GLOBAL = false, Y2_TO_GLOBAL = false;   // conv1 / conv2 results stay in LDS
+  static constexpr int W_KSTEP_BYTES = M * 64;
+  static constexpr unsigned W1_BYTES = M * C * 2, W2_BYTES = 9 * M * M * 2, W3_BYTES = C * M * 2;
   static constexpr int HT = pow2_at_least(cmax(2 * R1MAX, PPW * (S + 2) * (S + 2) + 1));  // hash table slots
   // LDS map (bytes)
   static constexpr int OFF_HKEY = 0;                            // int  [HT]     pixel+1 or 0
@@ -209,21 +217,31 @@ __device__ __forceinline__ void barrier_keep_vm_n(int n) {
 }
 
 // conv1's stream of global-memory operations per wave, in program order (they complete in
-// order):  W(0) X(0) W(1) X(1) X(2) .. X(D-1) | chunk 0: W(2) X(D) | chunk 1: W(3) X(D+1) | ...
-// W(c) = the NWL weight fragments of chunk c, X(c) = the NXL x loads of chunk c, D = chunks
-// of x requested ahead.  The barrier that opens chunk ch needs W(ch) and X(ch) complete;
-// this is the number of operations issued after the younger of the two, which may stay in flight.
-constexpr int conv1_keep_in_flight(int ch, int nch, int d, int nwl, int nxl) {
-  int after_w = -1, after_x = -1;          // operations issued after W(ch) / after X(ch)
+// order), for a weight ring of WD chunks and XD chunks of x requested ahead:
+//   prologue   c = 0, 1, ..:  W(c) if c < WD,  X(c) if c < XD
+//   chunk ch   (barrier, matrix work, and between the MFMAs)  W(ch + WD),  then  X(ch + XD)
+// (with the ring filled ahead of the phase -- HOISTED -- the prologue is W(0..WD-1) and then X(0..XD-1)).
+// W(c) = the NWL weight fragments of chunk c, X(c) = the NXL x loads of chunk c.  The barrier
+// that opens chunk ch needs W(ch) and X(ch) complete; this is the number of operations issued
+// after the younger of the two, which may stay in flight.
+constexpr int conv1_keep_in_flight(int ch, int nch, int wd, int xd, int nwl, int nxl, bool w_first = false) {
+  int after_w = -1, after_x = -1;          // operations issued up to and including W(ch) / X(ch)
   int total = 0;
   auto issue = [&](bool is_w, int c, int n) {
     if (c >= nch) return;
     total += n;
     if (c == ch) { if (is_w) after_w = total; else after_x = total; }
   };
-  issue(true, 0, nwl); issue(false, 0, nxl); issue(true, 1, nwl);
-  for (int c = 1; c < d; ++c) issue(false, c, nxl);
-  for (int c = 0; c < ch; ++c) { issue(true, c + 2, nwl); issue(false, c + d, nxl); }
+  if (w_first) {                           // the ring was filled before the phase: all of W(0..wd-1), then the x chunks
+    for (int c = 0; c < wd; ++c) issue(true, c, nwl);
+    for (int c = 0; c < xd; ++c) issue(false, c, nxl);
+  } else {
+    for (int c = 0; c < (wd > xd ? wd : xd); ++c) {
+      if (c < wd) issue(true, c, nwl);
+      if (c < xd) issue(false, c, nxl);
+    }
+  }
+  for (int c = 0; c < ch; ++c) { issue(true, c + wd, nwl); issue(false, c + xd, nxl); }
   const int last = after_w > after_x ? after_w : after_x;
   return total - last;
 }
@@ -262,10 +280,28 @@ __device__ __forceinline__ bf16x8 buf_load16(rsrc_t r, int lane_bytes, int unifo
 // x reaches LDS by direct global->LDS loads (16 bytes per lane, a wave fills 8 rows x 128 B;
 // the lane picks the global chunk whose swizzled position it writes), three stages deep;
 // the weights of the next two chunks are always in flight in registers.
-template <class K, int NB1>
-__device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_cp b1s, l_i32_cp rowpix,
-                                                      l_bf16_p xs, l_bf16_p y1s, int tid, int wave) {
-  constexpr int C = K::C, M = K::M, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
+// The weight ring of conv1: WD chunks of KS k-steps, NBW1 fragments each.
+template <class K>
+struct Conv1Ring { bf16x8 w[K::WD * (K::KC / 32)][K::NBW1]; };
+// Requests chunks 0 .. WD-1 (a kernel that has other latencies to wait for does this first).
+template <class K>
+__device__ __forceinline__ void conv1_ring_fill(Conv1Ring<K>& ring, g_bf16_p W1, int tid, int wave) {
+  const rsrc_t wrs = make_rsrc(W1, K::W1_BYTES);
+  const int lane16 = (tid & 63) * 16, wbase = (uni(wave) % K::WC1) * K::NBW1 * 1024;
+#pragma unroll
+  for (int t = 0; t < K::WD * (K::KC / 32); ++t)
+#pragma unroll
+    for (int j = 0; j < K::NBW1; ++j)
+      ring.w[t][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * K::W_KSTEP_BYTES);
+}
+
+// HOISTED: `ring` arrives filled by conv1_ring_fill.  yg / nrows: with K::Y1_TO_GLOBAL the result rows
+// go straight to memory, row r < nrows to yg + rowpix[r] * K::YG_PITCH (+ channel).
+template <class K, int NB1, bool HOISTED>
+__device__ LASNET_PHASE_INLINE void conv1_core(Conv1Ring<K>& ring, g_bf16_p x, g_bf16_p W1, l_f32_cp b1s,
+                                               l_i32_cp rowpix, l_bf16_p xs, l_bf16_p y1s, int tid, int wave,
+                                               AS_GLOBAL __bf16* yg = nullptr, int nrows = 0) {
+  constexpr int C = K::C, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
   constexpr int RB = cdiv(NB1, K::WR1);                   // row blocks of this wave (last may be padding)
   constexpr int NGRP = NB1 * 2, NXL = cdiv(NGRP, K::NW);  // 8-row groups; x loads per wave per chunk
   constexpr int NWL = KS * NBW;                           // weight loads per wave per chunk
@@ -316,14 +352,15 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
                    : "memory");
     }
   };
-  // weights: ring of two chunks, refilled in place
-  const rsrc_t wrs = make_rsrc(W1, (unsigned)(M * C * 2));
+  // weights: ring of WD chunks, refilled in place
+  constexpr int WD = K::WD;
+  const rsrc_t wrs = make_rsrc(W1, K::W1_BYTES);
   const int wbase = (wc * NBW) * 1024;                     // bytes, wave-uniform
-  bf16x8 w[2 * KS][NBW];
+  auto& w = ring.w;
   auto wload = [&](int slot, int kstep) {
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * (M * 64));
+      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * K::W_KSTEP_BYTES);
   };
   int boff[RB][KS];                                       // LDS offsets of this lane's B fragments
 #pragma unroll
@@ -336,16 +373,17 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
   // prologue of the stream (see conv1_keep_in_flight for the order)
   constexpr int XD = K::XD;
 #pragma unroll
-  for (int t = 0; t < KS; ++t) wload(t, t);
-  __builtin_amdgcn_sched_barrier(0);
-  issue_x(0);
-  __builtin_amdgcn_sched_barrier(0);
+  for (int c = 0; c < (WD > XD ? WD : XD); ++c) {
+    if (!HOISTED && c < WD && c < NCH) {
 #pragma unroll
-  for (int t = KS; t < 2 * KS; ++t) wload(t, t);
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int c = 1; c < XD; ++c) issue_x(c);
-  __builtin_amdgcn_sched_barrier(0);
+      for (int t = 0; t < KS; ++t) wload(c * KS + t, c * KS + t);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (c < XD) {
+      issue_x(c);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
 
   // B fragments are read one k-step ahead of the MFMAs that use them (bcur/bnxt), so a
   // wave's LDS latency hides behind its own matrix work.
@@ -353,11 +391,10 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
   // fully unrolled: with a back edge the compiler's own waits for the weight registers fall
   // back to vmcnt(0), which would drain the x stream every other chunk
 #pragma unroll
-  for (int ch2 = 0; ch2 < NCH; ch2 += 2) {
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-      const int ch = ch2 + cc;
-      barrier_keep_vm_n(conv1_keep_in_flight(ch, NCH, XD, NWL, NXL));
+  for (int ch = 0; ch < NCH; ++ch) {
+    {
+      const int cc = ch % WD;                              // ring slot group of this chunk (constant after unrolling)
+      barrier_keep_vm_n(conv1_keep_in_flight(ch, NCH, WD, XD, NWL, NXL, HOISTED));
       __builtin_amdgcn_sched_barrier(0);
       l_bf16_cp xb = xs + (ch % K::NSTG) * K::STAGE_ELEMS;
 #pragma unroll
@@ -372,7 +409,7 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
         for (int i = 0; i < RB; ++i)
 #pragma unroll
           for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[cc * KS + s][j], bcur[i], acc[i][j]);
-        if (ch + 2 < NCH) wload(cc * KS + s, (ch + 2) * KS + s);
+        if (ch + WD < NCH) wload(cc * KS + s, (ch + WD) * KS + s);
         __builtin_amdgcn_sched_barrier(0);
         if (s + 1 < KS) {
 #pragma unroll
@@ -385,6 +422,8 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  // (y1s may lie inside the x stages: every wave must have read its last chunk first)
+  if constexpr (K::Y1_IN_XS) __syncthreads();
   // epilogue: ReLU, round to bf16; 8 channels (one 16-byte chunk) per LDS store where NBW allows
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
@@ -394,7 +433,15 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v], 0.f);
-    if constexpr (NBW % 2 == 0) {
+    if constexpr (K::Y1_TO_GLOBAL) {
+      static_assert(!K::Y1_TO_GLOBAL || NBW % 2 == 0, "16-byte pieces");
+      if (row < nrows) {
+        AS_GLOBAL __bf16* dst = yg + (size_t)rowpix[row] * K::YG_PITCH;
+#pragma unroll
+        for (int j = 0; j < NBW; j += 2)
+          *reinterpret_cast<AS_GLOBAL bf16x8*>(dst + lane_channel(chb, NBW, j, lg, 0)) = join8(o[j], o[j + 1]);
+      }
+    } else if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
         *reinterpret_cast<AS_LDS bf16x8*>(y1s + swz(row, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, row, K::YMASK)) = join8(o[j], o[j + 1]);
@@ -408,11 +455,36 @@ __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_c
   }
 }
 
+template <class K, int NB1>
+__device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_cp b1s, l_i32_cp rowpix,
+                                                l_bf16_p xs, l_bf16_p y1s, int tid, int wave) {
+  Conv1Ring<K> ring;
+  conv1_core<K, NB1, false>(ring, x, W1, b1s, rowpix, xs, y1s, tid, wave);
+}
+
 // ---- phase 2: conv3x3 as an implicit GEMM over the 9 taps, y1 rows from LDS ---------------
-template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16_cp winrow, l_bf16_cp y1s,
-                                                      l_bf16_p y2s, int nq, int tid, int wave) {
-  constexpr int M = K::M, S = K::S, T = K::T, WW = K::WW;
+// The weight ring of conv2: the next RD2 k-steps, NBW2 fragments each.
+template <class K>
+struct Conv2Ring { bf16x8 w[K::RD2][K::NBW2]; };
+template <class K>
+__device__ __forceinline__ void conv2_ring_fill(Conv2Ring<K>& ring, g_bf16_p W2, int tid, int wave) {
+  const rsrc_t wrs = make_rsrc(W2, K::W2_BYTES);
+  const int lane16 = (tid & 63) * 16, wbase = (uni(wave) % K::WC2) * K::NBW2 * 1024;
+#pragma unroll
+  for (int t = 0; t < K::RD2; ++t)
+#pragma unroll
+    for (int j = 0; j < K::NBW2; ++j)
+      ring.w[t][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * K::W_KSTEP_BYTES);
+}
+
+// HOISTED: `ring` arrives holding k-steps 0 .. RD-1 and is left holding them again (the refills wrap
+// around), ready for another pass.  yg: with K::Y2_TO_GLOBAL the result rows go straight to memory,
+// row q < nq to yg + q * K::YG_PITCH (+ channel).
+template <class K, int NB2, bool HOISTED>
+__device__ LASNET_PHASE_INLINE void conv2_core(Conv2Ring<K>& ring, g_bf16_p W2, l_f32_cp b2s, l_i16_cp winrow,
+                                               l_bf16_cp y1s, l_bf16_p y2s, int nq, int tid, int wave,
+                                               AS_GLOBAL __bf16* yg = nullptr) {
+  constexpr int S = K::S, T = K::T, WW = K::WW;
   constexpr int NBW = K::NBW2, MS = K::MS, RD = K::RD2, NSTEP = 9 * MS;
   constexpr int RB = cdiv(NB2, K::WR2);
   const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
@@ -437,16 +509,25 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16
       wpos[i] = slot * WW + (r / S) * T + r % S;
     }
   }
-  const rsrc_t wrs = make_rsrc(W2, (unsigned)(9 * M * M * 2));
+  const rsrc_t wrs = make_rsrc(W2, K::W2_BYTES);
   const int wbase = (wc * NBW) * 1024;                     // bytes, wave-uniform
-  bf16x8 w[RD][NBW];                                       // weights of the next RD k-steps, refilled in place
+  auto& w = ring.w;                                        // weights of the next RD k-steps, refilled in place
   auto wload = [&](int slot, int kstep) {
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * (M * 64));
+      w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + kstep * K::W_KSTEP_BYTES);
   };
+  if constexpr (!HOISTED) {
 #pragma unroll
-  for (int t = 0; t < RD; ++t) wload(t, t);
+    for (int t = 0; t < RD; ++t) wload(t, t);
+  }
+  // The caller may have left the direct global->LDS loads of y1 in flight and the row tables unsynchronised:
+  // everything this wave has requested so far must have landed, and every wave must have got here.
+  if constexpr (K::ACTS_BARRIER) {
+    __builtin_amdgcn_sched_barrier(0);
+    barrier_keep_vm<HOISTED ? 0 : RD * NBW>();
+    __builtin_amdgcn_sched_barrier(0);
+  }
   auto lookup = [&](int (&br)[RB], int tap) {
     const int toff = (tap / 3) * T + tap % 3;
 #pragma unroll
@@ -483,7 +564,7 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16
       for (int i = 0; i < RB; ++i)
 #pragma unroll
         for (int j = 0; j < NBW; ++j) acc[i][j] = mfma16(w[tt][j], bcur[i], acc[i][j]);
-      if (t + RD < NSTEP) wload(tt, t + RD);
+      if (HOISTED || t + RD < NSTEP) wload(tt, (t + RD) % NSTEP);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < RB; ++i) bcur[i] = bnxt[i];
@@ -497,52 +578,92 @@ __device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v) o[j][v] = (__bf16)fmaxf(acc[i][j][v], 0.f);
-    if constexpr (NBW % 2 == 0) {
+    if constexpr (K::Y2_TO_GLOBAL) {
+      static_assert(!K::Y2_TO_GLOBAL || NBW % 2 == 0, "16-byte pieces");
+      if (q < nq) {
+#pragma unroll
+        for (int j = 0; j < NBW; j += 2)
+          *reinterpret_cast<AS_GLOBAL bf16x8*>(yg + (size_t)q * K::YG_PITCH + lane_channel(chb, NBW, j, lg, 0)) = join8(o[j], o[j + 1]);
+      }
+    } else if constexpr (NBW % 2 == 0) {
 #pragma unroll
       for (int j = 0; j < NBW; j += 2)
-        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY, lane_channel(chb, NBW, j, lg, 0) >> 3, q, K::YMASK)) = join8(o[j], o[j + 1]);
+        *reinterpret_cast<AS_LDS bf16x8*>(y2s + swz(q, K::LDY2, lane_channel(chb, NBW, j, lg, 0) >> 3, q, K::YMASK2)) = join8(o[j], o[j + 1]);
     } else {
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
         const int c = lane_channel(chb, NBW, j, lg, 0);
-        *reinterpret_cast<AS_LDS bf16x4*>(y2s + swz(q, K::LDY, c >> 3, q, K::YMASK) + (c & 7)) = o[j];
+        *reinterpret_cast<AS_LDS bf16x4*>(y2s + swz(q, K::LDY2, c >> 3, q, K::YMASK2) + (c & 7)) = o[j];
       }
     }
   }
 }
 
-// ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
 template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_cp b3s, l_i32_cp pixq,
-                                                      l_bf16_cp y2s, l_bf16_p tscratch, AS_GLOBAL __bf16* out,
-                                                      int post_relu, int tid, int wave) {
+__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16_cp winrow, l_bf16_cp y1s,
+                                                l_bf16_p y2s, int nq, int tid, int wave) {
+  Conv2Ring<K> ring;
+  conv2_core<K, NB2, false>(ring, W2, b2s, winrow, y1s, y2s, nq, tid, wave);
+}
+
+// ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
+// The weight ring of conv3: the next RD3 k-steps of NB3 fragments; a wave's stream is contiguous over
+// (pass, k-step, tile).  wc0: wave columns that other workgroups take (output channels split across workgroups).
+template <class K>
+struct Conv3Ring { bf16x8 w[K::RD3][K::NB3]; };
+template <class K>
+__device__ __forceinline__ void conv3_ring_fill(Conv3Ring<K>& ring, g_bf16_p W3, int tid, int wave, int wc0 = 0) {
+  const rsrc_t wrs = make_rsrc(W3, K::W3_BYTES);
+  const int lane16 = (tid & 63) * 16;
+  const int wbase = ((wc0 + uni(wave) % K::WC3) * (K::NBT3 / K::NB3)) * K::MS * K::NB3 * 1024;
+#pragma unroll
+  for (int t = 0; t < K::RD3; ++t)
+#pragma unroll
+    for (int j = 0; j < K::NB3; ++j)
+      ring.w[t][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * (K::NB3 * 1024));
+}
+
+// HOISTED: `ring` arrives holding steps 0 .. RD-1 and is left holding them again (the refills wrap around).
+template <class K, int NB2, bool HOISTED>
+__device__ LASNET_PHASE_INLINE void conv3_core(Conv3Ring<K>& ring, g_bf16_p x, g_bf16_p W3, l_f32_cp b3s,
+                                               l_i32_cp pixq, l_bf16_cp y2s, l_bf16_p tscratch,
+                                               AS_GLOBAL __bf16* out, int post_relu, int tid, int wave, int wc0 = 0) {
   constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
   constexpr int NPASS = K::NBT3 / NB, NSTEP = NPASS * MS;
   constexpr int RB = cdiv(NB2, K::WR3);
   const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
   const int lane16 = lane * 16;
   wave = uni(wave);
-  const int wr = wave / K::WC3, wc = wave % K::WC3;
+  // wc0: wave columns that other workgroups take (when the output channels are split across workgroups)
+  const int wr = wave / K::WC3, wc = wc0 + wave % K::WC3;
   const float floor_ = post_relu ? 0.f : -__builtin_inff();   // ReLU after the add, or nothing
   int pq[RB];
   FragRow fr[RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i) {
     const int bq = (wr + K::WR3 * i) * 16 + l16;
-    pq[i] = pixq[bq];
     fr[i] = frag_row(bq, K::LDY, lg, bq, K::YMASK);
   }
   // this wave's weight stream is contiguous over (pass, k-step, tile)
-  const rsrc_t wrs = make_rsrc(W3, (unsigned)(C * K::M * 2));
+  const rsrc_t wrs = make_rsrc(W3, K::W3_BYTES);
   const int wbase = (wc * NPASS) * MS * NB * 1024;         // bytes, wave-uniform
-  bf16x8 w[RD][NB];
+  auto& w = ring.w;
   auto wload = [&](int slot, int t) {
 #pragma unroll
     for (int j = 0; j < NB; ++j)
       w[slot][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * (NB * 1024));
   };
+  if constexpr (!HOISTED) {
 #pragma unroll
-  for (int t = 0; t < RD; ++t) wload(t, t);
+    for (int t = 0; t < RD; ++t) wload(t, t);
+  }
+  if constexpr (K::ACTS_BARRIER) {                         // as in conv2: y2 rows requested by the caller, pixq unsynchronised
+    __builtin_amdgcn_sched_barrier(0);
+    barrier_keep_vm<HOISTED ? 0 : RD * NB>();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int i = 0; i < RB; ++i) pq[i] = pixq[(wr + K::WR3 * i) * 16 + l16];
   // The residual comes from HBM, the weights from L2, and a wave's loads complete in issue order:
   // a weight fragment requested after a residual load cannot be used before that load has landed.
   // So a pass's residual is requested as early as its registers allow, straight after the weights
@@ -584,7 +705,7 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_c
         for (int j = 0; j < NB; ++j) acc[i][j] = mfma16(w[s % RD][j], bcur[i], acc[i][j]);
       // refill with the step RD ahead (the stream runs on into the next pass; past its end the
       // last step is re-read, unused)
-      wload(s % RD, min(pass * MS + s + RD, NSTEP - 1));
+      wload(s % RD, HOISTED ? (pass * MS + s + RD) % NSTEP : min(pass * MS + s + RD, NSTEP - 1));
       __builtin_amdgcn_sched_barrier(0);
       if (s + 1 < MS) {
 #pragma unroll
@@ -636,6 +757,14 @@ __device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_c
       }
     }
   }
+}
+
+template <class K, int NB2>
+__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_cp b3s, l_i32_cp pixq,
+                                                l_bf16_cp y2s, l_bf16_p tscratch, AS_GLOBAL __bf16* out,
+                                                int post_relu, int tid, int wave) {
+  Conv3Ring<K> ring;
+  conv3_core<K, NB2, false>(ring, x, W3, b3s, pixq, y2s, tscratch, out, post_relu, tid, wave);
 }
 
 template <class K>

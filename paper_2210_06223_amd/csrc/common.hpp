@@ -54,6 +54,21 @@ struct MfmaVariant {
 };
 int device_cu_count();
 
+// The tiled schedule (three kernels, y1 and y2 through a workspace) of one (C, M); any patch size.
+// It reads the same packed weight buffer as the fused kernels of that (C, M).
+struct TiledVariant {
+  int C, M;
+  bool preferred;                               // the library's own choice for this shape (else only on request)
+  bool (*takes)(const Geom& g);                 // does the map fit its image groups?
+  size_t (*workspace_bytes)(const Geom& g);
+  hipError_t (*prepare)();
+  hipError_t (*launch)(const Geom& g, const void* x, const int32_t* idx, const int32_t* count,
+                       const uint8_t* cellmask, const void* packed, const float* b1, const float* b2,
+                       const float* b3, void* out, bool post_relu, void* workspace, hipStream_t st);
+};
+// The tiled variant that takes this call, or nullptr (then the fused kernel runs).
+const TiledVariant* find_tiled(const Geom& g);
+
 // Matrix-core kernel: only for the (C, M, S) it was instantiated for.  It reads the three
 // weight tensors from one buffer of mfma_packed_bytes() that launch_pack() fills.
 bool mfma_supported(int C, int M, int S);

@@ -23,6 +23,12 @@ def _cfg(base, **kw):
     return synth.CONFIGS[base].with_(**kw)
 
 
+def _tiled(cfg):
+    """Whether the library runs this shape on the tiled schedule (three kernels and a workspace)."""
+    return B.lib().lasnet_workspace_bytes(B.LASNET_BF16 if cfg.dtype == "bf16" else B.LASNET_F32,
+                                          cfg.N, cfg.H, cfg.W, cfg.C, cfg.M, cfg.S) > 0
+
+
 def _oracle_w(inp):
     d = inp.f64
     return (d["W1"], d["b1"], d["W2"], d["b2"], d["W3"], d["b3"])
@@ -224,6 +230,9 @@ MFMA_CASES = [
 def test_mfma_kernel_matches_oracle(cfg, k):
     assert B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, cfg.S) == 1
     _run_case(cfg, k=k)
+    if _tiled(cfg):                                            # the shape has both schedules: each on request too
+        _run_case(cfg, k=k, flags=B.LASNET_FORCE_FUSED)
+        _run_case(cfg, k=k, flags=B.LASNET_FORCE_TILED)
 
 
 @pytest.mark.parametrize("cfg,k", MFMA_CASES[:1] + MFMA_CASES[2:3] + MFMA_CASES[4:5] + MFMA_CASES[7:9] + MFMA_CASES[10:11],
@@ -234,6 +243,11 @@ def test_mfma_extremes_and_flags(cfg, k):
     _run_case(cfg, k=1)
     _run_case(cfg, k=k, flags=B.LASNET_POST_RELU)
     _run_case(cfg, k=k, flags=B.LASNET_FORCE_GENERIC)          # scalar kernel on the same shape
+    if _tiled(cfg):
+        for forced in (B.LASNET_FORCE_FUSED, B.LASNET_FORCE_TILED):
+            for kk in (0, cfg.P, 1):
+                _run_case(cfg, k=kk, flags=forced)
+            _run_case(cfg, k=k, flags=forced | B.LASNET_POST_RELU)
 
 
 @pytest.mark.parametrize("structure", ["iid", "blob"])
@@ -350,7 +364,9 @@ def test_headline_workload_full_size_matches_oracle():
     """ResNet-101 stage 3, 14x14x1024, M=256, S=2, N=128, r=0.5: masker -> index list -> block,
     device-resident count, every output element against the oracle."""
     cfg = synth.CONFIGS["stage3_b128"]
+    assert _tiled(cfg)
     _run_case(cfg, k=cfg.P // 2)
+    _run_case(cfg, k=cfg.P // 2, flags=B.LASNET_FORCE_TILED)
 
 
 @pytest.mark.parametrize("name", ["stage3_b128", "stage2_b128", "stage1_b64", "stage4_b128"])
@@ -400,6 +416,10 @@ def test_mfma_kernels_on_non_square_maps(cfg, k):
     assert B.lasnet_has_fast_path(torch.bfloat16, cfg.C, cfg.M, cfg.S) == 1
     _run_case(cfg, k=k)
     _run_case(cfg, k=cfg.P)
+    if _tiled(cfg):
+        for forced in (B.LASNET_FORCE_FUSED, B.LASNET_FORCE_TILED):
+            _run_case(cfg, k=k, flags=forced)
+            _run_case(cfg, k=cfg.P, flags=forced)
 
 
 @pytest.mark.parametrize("cfg", [_cfg("stage3_b128", N=2, name="s3_hyg"), _cfg("stage1_b64", N=1, name="s1_hyg"),
@@ -460,13 +480,14 @@ def test_ratio_sweep_index_lists_at_full_size(name):
             idx = torch.zeros((cfg.P,), dtype=torch.int32, device="cuda")
             idx[: len(il)] = torch.from_numpy(il).cuda()
             count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
-            out = d["x"].clone()                                   # what the masker's pass-through leaves
-            B.lasnet_sparse_bottleneck_packed(d["x"], idx, count, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
-                                              out=out, flags=B.LASNET_SKIP_IDENTITY)
-            torch.cuda.synchronize()
             ref = O.masked_output(inp.f64["x"], f, mask, cfg.S)
             up = np.broadcast_to(O.upsample_mask(mask, cfg.S)[..., None], ref.shape)
-            U.assert_block_close(out, ref, d["x"], up, cfg.dtype, "%s r=%g %s" % (cfg.name, r, structure))
+            for flags in ((B.LASNET_FORCE_FUSED, B.LASNET_FORCE_TILED) if _tiled(cfg) else (0,)):
+                out = d["x"].clone()                               # what the masker's pass-through leaves
+                B.lasnet_sparse_bottleneck_packed(d["x"], idx, count, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
+                                                  out=out, flags=B.LASNET_SKIP_IDENTITY | flags)
+                torch.cuda.synchronize()
+                U.assert_block_close(out, ref, d["x"], up, cfg.dtype, "%s r=%g %s flags %d" % (cfg.name, r, structure, flags))
 
 
 # ------------------------------------------------------------------ the check build
@@ -485,10 +506,58 @@ def test_check_build_with_drained_barriers_is_bit_identical(monkeypatch):
         il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, k / cfg.P, seed=cfg.seed + 1000)
         idx = torch.from_numpy(il).cuda() if len(il) else torch.zeros(1, dtype=torch.int32, device="cuda")
         count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
-        outs = []
-        for L in (B.lib(), alt):
-            monkeypatch.setattr(B, "_lib", L)
-            outs.append(B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d)))
-            torch.cuda.synchronize()
-        monkeypatch.undo()
-        assert np.array_equal(U.bits(outs[0]), U.bits(outs[1])), cfg.name
+        for flags in ((B.LASNET_FORCE_FUSED, B.LASNET_FORCE_TILED) if _tiled(cfg) else (0,)):
+            outs = []
+            for L in (B.lib(), alt):
+                monkeypatch.setattr(B, "_lib", L)
+                outs.append(B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), flags=flags))
+                torch.cuda.synchronize()
+            monkeypatch.undo()
+            assert np.array_equal(U.bits(outs[0]), U.bits(outs[1])), (cfg.name, flags)
+
+
+# ------------------------------------------------------------------ the explicit entry (caller's workspace and mask)
+@pytest.mark.parametrize("cfg", [_cfg("stage3_b128", N=5, name="s3_planned"), _cfg("stage4_b128", N=7, name="s4_planned"),
+                                 _cfg("stage3_b128", N=3, S=7, name="s3S7_planned"),
+                                 _cfg("stage2_b128", N=2, name="s2_planned")], ids=lambda c: c.name)
+def test_planned_entry_with_callers_workspace_and_mask(cfg):
+    """lasnet_sparse_bottleneck_planned: packed weights, workspace and (optionally) the masker's byte mask
+    from the caller.  With and without the mask, and shuffled lists, the output is the same bits; and it
+    matches the oracle."""
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    k = int(round(cfg.r * cfg.P))
+    bm = U.calibrate(inp, k)
+    mask_o, idx_o, count_o, _ = O.masker(inp.f64["x"], inp.f64["Wm"], bm, cfg.S, 0.0)
+    mask, idx, count = B.lasnet_masker(d["x"], d["Wm"], bm, cfg.S, 0.0)
+    packed = B.lasnet_pack_weights(cfg.S, d["W1"], d["W2"], d["W3"])
+    need = B.lasnet_workspace_bytes(d["x"], cfg.M, cfg.S)
+    assert (need > 0) == _tiled(cfg)
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda") if need else None
+    forced = B.LASNET_FORCE_TILED if need else 0               # the three-kernel schedule wherever the shape has one
+    if ws is not None:
+        ws = ws[(-ws.data_ptr()) % 256:][:need]
+    outs = []
+    for m in (None, mask):
+        out = torch.full_like(d["x"], 777.0)
+        out.copy_(d["x"])
+        B.lasnet_sparse_bottleneck_planned(d["x"], idx, count, m, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out, ws,
+                                           flags=B.LASNET_SKIP_IDENTITY | forced)
+        torch.cuda.synchronize()
+        outs.append(out)
+    perm = torch.randperm(k, device="cuda")
+    idx_s = idx.clone(); idx_s[:k] = idx[:k][perm]
+    out = d["x"].clone()
+    B.lasnet_sparse_bottleneck_planned(d["x"], idx_s, count, None, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out, ws,
+                                       flags=B.LASNET_SKIP_IDENTITY | forced)
+    torch.cuda.synchronize()
+    outs.append(out)
+    assert np.array_equal(U.bits(outs[0]), U.bits(outs[1])) and np.array_equal(U.bits(outs[0]), U.bits(outs[2]))
+    ref = O.sparse_bottleneck(inp.f64["x"], mask_o, cfg.S, *_oracle_w(inp))
+    up = np.broadcast_to(O.upsample_mask(mask_o, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(outs[0], ref, d["x"], up, cfg.dtype, cfg.name)
+    if need:                                                   # a workspace that is too small is refused
+        with pytest.raises(B.LasnetError) as e:
+            B.lasnet_sparse_bottleneck_planned(d["x"], idx, count, None, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
+                                               out, ws[: need - 256], flags=forced)
+        assert e.value.status == B.LASNET_EINVAL
