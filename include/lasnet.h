@@ -262,6 +262,18 @@ LASNET_API int lasnet_dense_bottleneck(const lasnet_tensor* x, int M,
  * negative status if even the generic kernel cannot take it.  Host-only query. */
 LASNET_API int lasnet_has_fast_path(int dtype, int C, int M, int S);
 
+/*
+ * Microbenchmarks for the measurement harness (what this GPU sustains, beside the data-sheet peaks the
+ * roofline fractions are quoted against).  The caller times them with events on its stream.
+ *   lasnet_microbench_mfma   every SIMD issues independent bf16 16x16x32 MFMAs from registers, `iters`
+ *                            rounds of 16; returns the FLOPs of the launch (2 per multiply-add), 0 on
+ *                            error.  sink: any device buffer of at least 2 KiB (never written).
+ *   lasnet_microbench_copy   out = in with the library's copy kernel; bytes a multiple of 16, both
+ *                            pointers 16-byte aligned (else LASNET_EINVAL).
+ */
+LASNET_API double lasnet_microbench_mfma(int iters, void* sink, void* hip_stream);
+LASNET_API int lasnet_microbench_copy(const void* in, void* out, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

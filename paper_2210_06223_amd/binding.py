@@ -28,6 +28,7 @@ EXPORTS = (
     "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
     "lasnet_sparse_bottleneck_packed", "lasnet_sparse_bottleneck_noalloc",
     "lasnet_workspace_bytes", "lasnet_sparse_bottleneck_planned",
+    "lasnet_microbench_mfma", "lasnet_microbench_copy",
 )
 
 
@@ -71,6 +72,10 @@ def load_library(path: str) -> ctypes.CDLL:
     L.lasnet_sparse_bottleneck_planned.restype = ip
     L.lasnet_sparse_bottleneck_planned.argtypes = [tp, vp, vp, vp, ip, ip, vp, vp, vp, vp, tp, ctypes.c_uint32,
                                                    vp, ctypes.c_size_t, vp]
+    L.lasnet_microbench_mfma.restype = ctypes.c_double
+    L.lasnet_microbench_mfma.argtypes = [ip, vp, vp]
+    L.lasnet_microbench_copy.restype = ip
+    L.lasnet_microbench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.lasnet_sparse_bottleneck_noalloc.restype = ip
     L.lasnet_sparse_bottleneck_noalloc.argtypes = L.lasnet_sparse_bottleneck_ex.argtypes
     L.lasnet_dense_bottleneck.restype = ip
@@ -341,3 +346,20 @@ def lasnet_sparse_bottleneck_packed(x: torch.Tensor, idx: Optional[torch.Tensor]
                                                _stream(stream))
     _check(st, "lasnet_sparse_bottleneck_packed")
     return out
+
+
+def lasnet_microbench_mfma(iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Launches the register-only bf16 MFMA loop; returns the FLOPs of the launch."""
+    f = lib().lasnet_microbench_mfma(int(iters), _ptr(sink), _stream(stream))
+    if f <= 0:
+        raise LasnetError(LASNET_EHIP, "lasnet_microbench_mfma")
+    return float(f)
+
+
+def lasnet_microbench_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
+    """dst = src with the library's copy kernel; returns the bytes copied."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must have the same size")
+    _check(lib().lasnet_microbench_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "lasnet_microbench_copy")
+    return nbytes

@@ -16,7 +16,7 @@ LIB = os.path.join(PKG, "liblasnet.so")
 LIB_CHECK = os.path.join(PKG, "liblasnet_check.so")
 CHECK_FLAGS = ("-DLASNET_DRAIN_AT_BARRIERS",)
 SOURCES = ["tiled_stages.hip", "mfma_stage3.hip", "mfma_stage2.hip", "mfma_stage1.hip", "mfma_stage4.hip",   # slowest first
-           "api.hip", "masker.hip", "bottleneck_generic.hip", "bottleneck_mfma.hip"]
+           "api.hip", "masker.hip", "bottleneck_generic.hip", "bottleneck_mfma.hip", "microbench.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

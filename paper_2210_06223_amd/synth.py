@@ -205,3 +205,49 @@ def make_index_list(N: int, G: int, GW: int, r_mean: float, seed: int,
     elif order != "ascending":
         raise ValueError(order)
     return idx
+
+
+# --------------------------------------------------------------------------- ResNet-101 body
+# Stage shapes of the ResNet-101 body on 224x224 inputs: (H = W, C, M, S, sparse blocks).  The first
+# block of every stage (projection shortcut; stride 2 from the second stage on) and the stem run
+# dense and are not part of the sparse path; S = (8, 4, 2, 1) per stage, the 7x7 stage pixel-level
+# (Sec. 4.2, Sec. 4.3).
+RESNET101_STAGES = ((56, 256, 64, 8, 2), (28, 512, 128, 4, 3), (14, 1024, 256, 2, 22), (7, 2048, 512, 1, 2))
+
+
+def make_chain_weights(seed: int = 4, stages=RESNET101_STAGES, w3_scale_mean: float = 0.25):
+    """Random-init weights of every SPARSE block of the body, in order, plus each block's target ratio.
+
+    Per block the recipe of make_block_inputs (He-normal, folded BN scale and bias, masker weights), with
+    one change: the folded scale of the LAST convolution is N(w3_scale_mean, w3_scale_mean / 10) instead
+    of N(1, 0.1) -- in a random-weight chain the residual branch is as large as the identity and the
+    variance of the activations would double with every block, which no trained network does.  Target
+    activation ratio of each block ~ U(0.3, 0.7).  Returns a list of dicts with fp32 arrays
+    (W1 [M,C], b1, W2 [M,3,3,M], b2, W3 [C,M], b3, Wm [C]), 'stage', 'H', 'C', 'M', 'S', 'r'.
+    """
+    root = np.random.SeedSequence([seed, 0xB0D1])
+    blocks = []
+    n_blocks = sum(s[4] for s in stages)
+    children = root.spawn(n_blocks)
+    bi = 0
+    for si, (H, C, M, S, nb) in enumerate(stages):
+        for _ in range(nb):
+            g = np.random.Generator(np.random.PCG64(children[bi]))
+            bi += 1
+
+            def normal(shape, std=1.0, mean=0.0):
+                return (g.standard_normal(shape, dtype=np.float32) * np.float32(std) + np.float32(mean)).astype(np.float32)
+
+            s1, s2 = normal((M,), 0.1, 1.0), normal((M,), 0.1, 1.0)
+            s3 = normal((C,), w3_scale_mean / 10.0, w3_scale_mean)
+            blk = {
+                "W1": normal((M, C), np.sqrt(2.0 / C)) * s1[:, None],
+                "W2": normal((M, 3, 3, M), np.sqrt(2.0 / (9 * M))) * s2[:, None, None, None],
+                "W3": normal((C, M), np.sqrt(2.0 / M)) * s3[:, None],
+                "b1": normal((M,), 0.1), "b2": normal((M,), 0.1), "b3": normal((C,), 0.1),
+                "Wm": normal((C,), 0.02),
+                "r": float(g.uniform(0.3, 0.7)),
+                "stage": si + 1, "H": H, "C": C, "M": M, "S": S,
+            }
+            blocks.append(blk)
+    return blocks
