@@ -132,9 +132,12 @@ LASNET_API int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, flo
  * (negative, or >= N*G*GW) is ignored; a count[0] beyond N*G*GW is read as N*G*GW.
  * idx == NULL means "all cells active" and count is then ignored (may be NULL).
  *
- * M: bottleneck width.  out: same shape and dtype as x, a different buffer: out->data ==
- * x->data gives LASNET_EALIAS, because a patch updated in place would corrupt the
- * neighbour read of an adjacent active patch.
+ * M: bottleneck width.  out: same shape and dtype as x.  Normally a different buffer: in the fused
+ * schedule a patch updated in place would corrupt the neighbour read of an adjacent active
+ * patch, so out->data == x->data gives LASNET_EALIAS there (and so do buffers that overlap
+ * without being the same, on every schedule).  On the tiled schedule (see "Schedules") out may BE x:
+ * the block is then updated in place, as App. B.1 (3) stores results into the residual map --
+ * inactive patches are simply not touched and no identity copy is made.
  * bf16: products on the matrix cores with fp32 accumulation; y1, y2 are rounded to bf16
  * (nearest even) between the convolutions, out is rounded once after the residual add.
  */

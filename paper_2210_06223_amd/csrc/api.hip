@@ -128,7 +128,6 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
   if (out->n != x->n || out->h != x->h || out->w != x->w || out->c != x->c ||
       out->dtype != x->dtype)
     return LASNET_ESHAPE;
-  if (x->n > 0 && out->data == x->data) return LASNET_EALIAS;
   const bool force_generic = (flags & LASNET_FORCE_GENERIC) != 0;
   if (dense) {
     S = dense_tile(x->dtype, x->h, x->w, x->c, M, force_generic);
@@ -160,6 +159,16 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
     if (tiled && !tiled->preferred && !(flags & LASNET_FORCE_TILED)) tiled = nullptr;
   }
   if ((flags & LASNET_FORCE_TILED) && !tiled) return LASNET_EUNSUPPORTED;
+  // out == x (update in place, as App. B.1 (3) stores into the residual map) is safe only on the tiled
+  // schedule: its last kernel reads and writes nothing but the active pixels' own elements, after the
+  // kernel that reads neighbours has finished.  In one kernel a patch updated in place would corrupt a
+  // neighbouring patch's window.  Buffers that overlap without being the same are never accepted.
+  const bool in_place = x->n > 0 && out->data == x->data;
+  if (x->n > 0 && !in_place) {
+    const uintptr_t a = (uintptr_t)x->data, b = (uintptr_t)out->data;
+    if (a < b + map_bytes && b < a + map_bytes) return LASNET_EALIAS;
+  }
+  if (in_place && !tiled) return LASNET_EALIAS;
   const size_t packed_need = (fast && !packed) ? round256(mfma_packed_bytes(x->c, M, S)) : 0;
   const size_t tiled_need = tiled ? tiled->workspace_bytes(g) : 0;
   if (pad.from_caller && tiled && (!pad.workspace || pad.workspace_bytes < tiled_need || ((uintptr_t)pad.workspace & 255)))
@@ -195,7 +204,7 @@ int run_block(const lasnet_tensor* x, const int32_t* idx, const int32_t* count, 
     }
     tiled_ws = ws + packed_need;
   }
-  if (!dense && idx && !(flags & LASNET_SKIP_IDENTITY)) {
+  if (!dense && idx && !in_place && !(flags & LASNET_SKIP_IDENTITY)) {
     e = launch_copy(x->data, out->data, map_bytes, st);
     if (e != hipSuccess) return LASNET_EHIP;
   }
@@ -244,7 +253,7 @@ const char* lasnet_status_string(int status) {
     case LASNET_EINVAL: return "invalid argument (null pointer, bad dtype, S or M)";
     case LASNET_ESHAPE: return "shape mismatch (S must divide H and W; out must match x)";
     case LASNET_EUNSUPPORTED: return "shape not supported by the built kernels";
-    case LASNET_EALIAS: return "out must not alias x";
+    case LASNET_EALIAS: return "out must not alias x (only the tiled schedule can update x in place)";
     case LASNET_EHIP: return "HIP runtime error or no gfx950 device";
     case LASNET_ETOOBIG: return "repacked weights exceed the fixed scratch array of lasnet_sparse_bottleneck_noalloc";
     default: return "unknown status";

@@ -806,10 +806,16 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
   // Workgroup b runs on XCD b % 8 (round-robin dispatch), and each XCD has its own L2.  Runs
   // that are neighbours in the list share window pixels, so XCD k takes a contiguous eighth
   // of the runs: the shared rows are then fetched into one L2 once, not into two.
+  // Within its eighth, an XCD's longer runs (one entry more than the others) go to its FIRST workgroups:
+  // when the launch takes more than one round of workgroups, a run that needs a second batch (a
+  // batch is cut when its windows share too little) then starts early instead of ending the launch.
   const int xcd = (int)blockIdx.x & 7, jx = (int)blockIdx.x >> 3;
-  const int tile = xcd * (nt >> 3) + min(xcd, nt & 7) + jx;   // jx < runs of this XCD because b < nt
-  const int tb = (int)(((long long)tile * nact) / nt);
-  const int te = (int)(((long long)(tile + 1) * nact) / nt);
+  const int first = xcd * (nt >> 3) + min(xcd, nt & 7);        // jx < runs of this XCD because b < nt
+  const int runs = (nt >> 3) + (xcd < (nt & 7) ? 1 : 0);
+  const int xb = (int)(((long long)first * nact) / nt), xe = (int)(((long long)(first + runs) * nact) / nt);
+  const int len0 = (xe - xb) / runs, extra = (xe - xb) - len0 * runs;
+  const int tb = xb + jx * len0 + min(jx, extra);
+  const int te = tb + len0 + (jx < extra ? 1 : 0);
 
   // the all-zero y1 row
   for (int i = tid; i < K::LDY / 8; i += K::NT)

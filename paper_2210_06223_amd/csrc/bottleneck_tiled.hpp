@@ -401,9 +401,9 @@ __global__ __launch_bounds__(256, 1) void tiled_conv2_kernel(
 // ---------------------------------------------------------------------------------------- T3
 template <class TC>
 __global__ __launch_bounds__(256, 1) void tiled_conv3_kernel(
-    Geom g, TiledGeom tg, const uint8_t* __restrict__ mask, int all_active, const __bf16* __restrict__ x,
+    Geom g, TiledGeom tg, const uint8_t* __restrict__ mask, int all_active, const __bf16* x,
     const __bf16* __restrict__ W3p, const float* __restrict__ b3, const __bf16* __restrict__ y2g,
-    __bf16* __restrict__ out, int post_relu) {
+    __bf16* out, int post_relu) {                          // out may be x: a lane reads and writes the same elements
   using K = typename TC::K3;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   int group, slice;

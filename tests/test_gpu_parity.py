@@ -561,3 +561,44 @@ def test_planned_entry_with_callers_workspace_and_mask(cfg):
             B.lasnet_sparse_bottleneck_planned(d["x"], idx, count, None, cfg.S, cfg.M, packed, d["b1"], d["b2"], d["b3"],
                                                out, ws[: need - 256], flags=forced)
         assert e.value.status == B.LASNET_EINVAL
+
+
+# ------------------------------------------------------------------ in place (tiled schedule only)
+@pytest.mark.parametrize("cfg,flags", [(_cfg("stage4_b128", N=5, name="s4_inplace"), 0),
+                                       (_cfg("stage3_b128", N=4, name="s3_inplace"), B.LASNET_FORCE_TILED)],
+                         ids=lambda v: getattr(v, "name", str(v)))
+def test_in_place_update_on_the_tiled_schedule(cfg, flags):
+    """out == x: the tiled schedule updates the active patches in place (its last kernel touches only
+    their own elements, after the kernel that reads neighbours); same bits as out of place, and the
+    oracle's result.  The fused schedule refuses."""
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=cfg.seed + 3)
+    idx = torch.from_numpy(il).cuda()
+    count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
+    for post in (0, B.LASNET_POST_RELU):
+        want = B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), flags=flags | post)
+        xin = d["x"].clone()
+        B.lasnet_sparse_bottleneck(xin, idx, count, cfg.S, *U.weights(d), out=xin, flags=flags | post)
+        torch.cuda.synchronize()
+        assert np.array_equal(U.bits(xin), U.bits(want))
+    mask = np.zeros(cfg.P, np.uint8); mask[il] = 1
+    mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
+    ref = O.sparse_bottleneck(inp.f64["x"], mask, cfg.S, *_oracle_w(inp), post_relu=True)
+    up = np.broadcast_to(O.upsample_mask(mask, cfg.S)[..., None], ref.shape)
+    U.assert_block_close(xin, ref, d["x"], up, cfg.dtype, cfg.name)
+    # dense block in place
+    xin = d["x"].clone()
+    B.lasnet_dense_bottleneck(xin, *U.weights(d), out=xin, flags=flags)
+    want = B.lasnet_dense_bottleneck(d["x"], *U.weights(d), flags=flags)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.bits(xin), U.bits(want))
+    # the one-kernel schedule cannot; overlapping but different buffers never
+    with pytest.raises(B.LasnetError) as e:
+        B.lasnet_sparse_bottleneck(xin, idx, count, cfg.S, *U.weights(d), out=xin, flags=B.LASNET_FORCE_FUSED)
+    assert e.value.status == B.LASNET_EALIAS
+    big = torch.zeros(d["x"].numel() + 8 * cfg.C, dtype=torch.bfloat16, device="cuda")
+    a = big[: d["x"].numel()].view_as(d["x"]); b = big[8 * cfg.C:].view_as(d["x"])
+    with pytest.raises(B.LasnetError) as e:
+        B.lasnet_sparse_bottleneck(a, idx, count, cfg.S, *U.weights(d), out=b, flags=flags)
+    assert e.value.status == B.LASNET_EALIAS
