@@ -169,7 +169,7 @@ def main():
 
         return inp, {k: to_dev(k, v) for k, v in inp.dev.items()}
 
-    def ratio_sweep(cfg, d, xs, outs, packed, dense_ms):
+    def ratio_sweep(cfg, d, xs, outs, packed, dense_ms, forced=0):
         """Block latency against the activation ratio: index lists fed directly (per-image ratios
         Beta-distributed around the mean), prepacked weights, identity pass-through not included (it lives
         in the masker call), against the dense block through the same entry."""
@@ -184,8 +184,14 @@ def main():
                 t = timed_loop(lambda i: B.lasnet_sparse_bottleneck_packed(
                     xs[i % len(xs)], idx_r, cnt_r, S, cfg.M, packed, d["b1"], d["b2"], d["b3"], out=outs[i % len(xs)],
                     flags=B.LASNET_SKIP_IDENTITY | forced), 50)
+                try:                 # the library's latency predictor (fitted constants, Sec. 3.3 / App. A in this chip's terms)
+                    from paper_2210_06223_amd import latency_model as LM
+                    sch = "tiled" if forced == B.LASNET_FORCE_TILED else "fused" if forced == B.LASNET_FORCE_FUSED else "auto"
+                    pred = LM.predict_us(il, cfg.N, cfg.H, cfg.W, cfg.C, cfg.M, S, sch) * 1e-3
+                except Exception:
+                    pred = None
                 pts.append({"r_mean": r, "structure": structure, "active": len(il), "r": len(il) / P,
-                            "block_ms": t, "latency_ratio_vs_dense": t / dense_ms})
+                            "block_ms": t, "latency_ratio_vs_dense": t / dense_ms, "predicted_ms": pred})
         # how far the curve is from affine in r: worst deviation of a point from the line through the end points
         for structure in ("iid", "blob"):
             q = [p for p in pts if p["structure"] == structure]
@@ -350,7 +356,7 @@ def main():
 
     sweeps = None
     if not args.no_sweep and fast:
-        sweeps = {cfg.name: ratio_sweep(cfg, d, xs, outs, packed, dense_packed_ms)}
+        sweeps = {cfg.name: ratio_sweep(cfg, d, xs, outs, packed, dense_packed_ms, forced)}
         sweeps_dense = {cfg.name: dense_packed_ms}
         if cfg.name != "stage2_b128" and args.ratio is None and args.workload == "stage3_b128":
             # the 28x28x512 block on which the ratio sweep is defined
