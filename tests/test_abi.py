@@ -115,6 +115,44 @@ def test_flag_and_status_values_match_the_header():
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     vals = {k: int(v) for k, v in re.findall(r"\b(LASNET_[A-Z0-9_]+)\s*=\s*(-?\d+)", text)}
     for name in ("LASNET_OK", "LASNET_EINVAL", "LASNET_ESHAPE", "LASNET_EUNSUPPORTED", "LASNET_EALIAS", "LASNET_EHIP",
-                 "LASNET_F32", "LASNET_BF16", "LASNET_POST_RELU", "LASNET_FORCE_GENERIC", "LASNET_SKIP_IDENTITY"):
+                 "LASNET_ETOOBIG", "LASNET_F32", "LASNET_BF16", "LASNET_POST_RELU", "LASNET_FORCE_GENERIC",
+                 "LASNET_SKIP_IDENTITY", "LASNET_FORCE_FUSED", "LASNET_FORCE_TILED"):
         assert name in vals, name
         assert getattr(B, name) == vals[name], name
+
+
+def test_schedules_workspace_query_and_planned_entry_argument_errors():
+    """Host-side answers about the two schedules: which shapes have a tiled one and what it needs, and
+    what the explicit entry refuses before any device call (fake pointers throughout)."""
+    L = B.lib()
+    bf = B.LASNET_BF16
+    # 14x14x1024 (one image per group) and 7x7x2048 (two per group): cell masks + y1 + y2
+    n, hw, m = 128, 196, 256
+    assert L.lasnet_workspace_bytes(bf, n, 14, 14, 1024, m, 2) == (6272 + 255) // 256 * 256 + 2 * n * hw * m * 2
+    assert L.lasnet_workspace_bytes(bf, 5, 7, 7, 2048, 512, 1) == 256 + 5 * 49 * 512 * 2 + 3 * 2 * 49 * 512 * 2
+    assert L.lasnet_workspace_bytes(bf, 4, 28, 28, 512, 128, 4) == 0          # fused only
+    assert L.lasnet_workspace_bytes(bf, 4, 28, 28, 1024, 256, 2) == 0         # an image does not fit a group
+    assert L.lasnet_workspace_bytes(B.LASNET_F32, 4, 14, 14, 1024, 256, 2) == 0
+    p = ctypes.c_void_p(0x10000)
+    x = B.lasnet_tensor(0x100000, 2, 14, 14, 1024, bf)
+    o = B.lasnet_tensor(0x900000, 2, 14, 14, 1024, bf)
+
+    def planned(packed=p, ws=ctypes.c_void_p(0x4000000), wsb=1 << 30, flags=B.LASNET_FORCE_TILED, xx=x, oo=o, S=2, M=256):
+        return L.lasnet_sparse_bottleneck_planned(ctypes.byref(xx), p, p, None, S, M, packed, p, p, p, ctypes.byref(oo),
+                                                  flags, ws, wsb, None)
+
+    assert planned(packed=None) == B.LASNET_EINVAL
+    assert planned(ws=None) == B.LASNET_EINVAL                                 # the tiled schedule needs a workspace
+    assert planned(wsb=1024) == B.LASNET_EINVAL                                # too small
+    assert planned(ws=ctypes.c_void_p(0x4000010)) == B.LASNET_EINVAL           # not 256-byte aligned
+    x2 = B.lasnet_tensor(0x100000, 2, 28, 28, 512, bf)
+    o2 = B.lasnet_tensor(0x900000, 2, 28, 28, 512, bf)
+    assert planned(xx=x2, oo=o2, S=4, M=128) == B.LASNET_EUNSUPPORTED          # no tiled schedule to force
+    # in place: refused where the one-kernel schedule would run
+    assert planned(xx=x, oo=x, flags=B.LASNET_FORCE_FUSED) == B.LASNET_EALIAS
+    assert planned(xx=x, oo=x, flags=0) == B.LASNET_EALIAS                     # 14x14x1024 defaults to the fused schedule
+    half = B.lasnet_tensor(0x100000 + 4096, 2, 14, 14, 1024, bf)
+    assert planned(xx=x, oo=half) == B.LASNET_EALIAS                           # overlapping, not the same
+    st = L.lasnet_sparse_bottleneck_noalloc(ctypes.byref(x), p, p, 2, 256, p, p, p, p, p, p, ctypes.byref(o),
+                                            B.LASNET_FORCE_TILED, None)
+    assert st == B.LASNET_EUNSUPPORTED                                         # that entry never runs the tiled schedule
