@@ -180,6 +180,15 @@ __device__ inline unsigned hash_pix(int pix) { return ((unsigned)pix * 265443576
 // Wave-uniform value -> scalar register, so that the compiler branches on it with scalar
 // branches instead of exec masks.
 __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+// The value, behind a barrier the optimiser cannot look through.  Each phase derives its lane
+// addresses from a fresh copy of the thread id: derived from the kernel's one copy they are all
+// hoisted to the kernel's top, where some forty of them stay live across every phase and push the
+// k-loops' weight rings into scratch memory (a reload from there in the middle of a k-loop also
+// waits for every weight load requested before it).
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
 
 // Calls f(integral_constant<n>) for the run-time n in [LO, HI]: the row-block count of a
 // phase becomes a compile-time constant, so each phase's inner loop is straight-line code.
@@ -921,18 +930,18 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     // ...); the count is rounded up to a multiple of WR, the extra blocks compute unused rows.
     dispatch_count<1, K::R1B / K::WR1>((nblk1 + K::WR1 - 1) / K::WR1, [&](auto nb) {
       conv1_phase<K, decltype(nb)::value * K::WR1>((g_bf16_p)x, (g_bf16_p)W1, (l_f32_cp)b1s, (l_i32_cp)rowpix,
-                                                   (l_bf16_p)xs, (l_bf16_p)y1s, tid, wave);
+                                                   (l_bf16_p)xs, (l_bf16_p)y1s, opaque(tid), wave);
     });
     __syncthreads();
     constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       conv2_phase<K, decltype(nb)::value * WR23>((g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s,
-                                                 (l_bf16_p)y2s, nq, tid, wave);
+                                                 (l_bf16_p)y2s, nq, opaque(tid), wave);
     });
     __syncthreads();
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq,
-                                                 (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, tid, wave);
+                                                 (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, opaque(tid), wave);
     });
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch
