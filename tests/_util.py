@@ -56,7 +56,7 @@ def assert_block_close(got: torch.Tensor, ref: np.ndarray, x: torch.Tensor, up_m
     """Active positions within tolerance, inactive positions bit-identical to x.
 
     Tolerance (derived in the design notes): |got - ref| <= rtol*|ref| + rtol*rms(ref_active),
-    and max|got - ref| <= rtol * max|ref|.
+    max|got - ref| <= rtol * max|ref|, and the relative L2 error over the active positions <= rtol.
     """
     rtol = RTOL[dtype]
     g = to_f64(got)
@@ -74,3 +74,5 @@ def assert_block_close(got: torch.Tensor, ref: np.ndarray, x: torch.Tensor, up_m
         assert worst <= 1.0, "%s: per-element error %.3g x bound (max abs err %.3g, rms %.3g)" % (
             what, worst, float(err.max()), rms)
         assert float(err.max()) <= rtol * float(np.abs(ra).max()), what + ": max-norm error"
+        rel_l2 = float(np.sqrt(np.sum(err * err) / max(np.sum(ra * ra), 1e-300)))
+        assert rel_l2 <= rtol, "%s: relative L2 error %.3g > %.3g" % (what, rel_l2, rtol)
