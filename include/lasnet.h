@@ -160,14 +160,15 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
  * Schedules.  Two matrix-core schedules exist, and the library picks by shape (Sec. 3.4 discusses
  * this choice of operator fusion against the activation rate; on this GPU the block shape decides):
  *   fused  one kernel: gather + conv1 + conv3x3 + conv3 + scatter-add, y1 and y2 never leave the CU.
- *          Used where the weights are small against the maps (ResNet-101 stages 1-2).
+ *          Used where a CU can afford to stream all weights per batch of patches (ResNet-101 stages 1-3).
  *   tiled  the paper's own operator split (Sec. 3.4, App. B.1): conv1 over the pixels that some
  *          active patch needs | gather + conv3x3 | conv3 + scatter-add, as three kernels with y1 and
  *          y2 passing through a workspace in device memory.  Built for 1024x256 channels on maps of
  *          up to 196 pixels (14x14) and 2048x512 channels on maps of up to 49 pixels (7x7), any patch
  *          size.  The library's own choice for 2048x512 (measured faster there at every activation
- *          rate); for 1024x256 the fused kernel measured faster at every rate, so the tiled one
- *          runs only with LASNET_FORCE_TILED.
+ *          rate); for 1024x256 the fused kernel measured faster below an activation rate of about 0.75
+ *          and the same above, so the tiled one runs only with LASNET_FORCE_TILED (a caller that
+ *          knows its rate is high, or that wants the in-place update).
  * Results are the same function of the inputs either way (same roundings: y1, y2 to bf16, out once).
  * The tiled schedule needs lasnet_workspace_bytes() of device memory (that query answers for every
  * shape that has a tiled schedule, chosen by default or not; 0 = none): lasnet_sparse_bottleneck[_ex],
@@ -253,7 +254,7 @@ LASNET_API int lasnet_sparse_bottleneck_noalloc(const lasnet_tensor* x, const in
  * The static block (activation rate 1, no masker): out = x + F(x) at every pixel -- the
  * l_stat that the paper's latency ratio r_l = l_dyn / l_stat is measured against (Sec. 4.2).
  * Runs the same kernels over tiles that cover the whole map.  flags: LASNET_POST_RELU,
- * LASNET_FORCE_GENERIC.
+ * LASNET_FORCE_GENERIC, LASNET_FORCE_FUSED, LASNET_FORCE_TILED.
  */
 LASNET_API int lasnet_dense_bottleneck(const lasnet_tensor* x, int M,
                             const void* W1, const float* b1,
