@@ -608,13 +608,6 @@ __device__ LASNET_PHASE_INLINE void conv2_core(Conv2Ring<K>& ring, g_bf16_p W2, 
   }
 }
 
-template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv2_phase(g_bf16_p W2, l_f32_cp b2s, l_i16_cp winrow, l_bf16_cp y1s,
-                                                l_bf16_p y2s, int nq, int tid, int wave) {
-  Conv2Ring<K> ring;
-  conv2_core<K, NB2, false>(ring, W2, b2s, winrow, y1s, y2s, nq, tid, wave);
-}
-
 // ---- phase 3: conv3 + b3 + residual, one rounding, stored at the patch's own pixels -------
 // The weight ring of conv3: the next RD3 k-steps of NB3 fragments; a wave's stream is contiguous over
 // (pass, k-step, tile).  wc0: wave columns that other workgroups take (output channels split across workgroups).
@@ -632,11 +625,35 @@ __device__ __forceinline__ void conv3_ring_fill(Conv3Ring<K>& ring, g_bf16_p W3,
       ring.w[t][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * (K::NB3 * 1024));
 }
 
+// The residual (x at the output pixels) of conv3's first pass, in the registers of the lanes that will add it.
+template <class K, int NB2>
+struct Conv3Residual { bf16x8 v[cdiv(NB2, K::WR3)][K::NB3 / 2]; };
+// Requests it.  The fused kernel does this at the start of conv2, a phase that reads no global memory but
+// its weights: the loads have landed long before conv3 starts (which otherwise opens with this wait), and
+// they run while the memory system is idle instead of beside conv3's stores.
+template <class K, int NB2>
+__device__ __forceinline__ void conv3_residual_request(Conv3Residual<K, NB2>& res, g_bf16_p x, l_i32_cp pixq,
+                                                       int tid, int wave, int wc0 = 0) {
+  const int lane = tid & 63, l16 = lane & 15, lg = lane >> 4;
+  wave = uni(wave);
+  const int wr = wave / K::WC3, wc = wc0 + wave % K::WC3;
+  const int chb = (wc * K::NBT3) * 16;
+#pragma unroll
+  for (int i = 0; i < cdiv(NB2, K::WR3); ++i) {
+    const int pq = pixq[(wr + K::WR3 * i) * 16 + l16];     // rows past the last pixel read pixel 0 (never stored)
+#pragma unroll
+    for (int j = 0; j < K::NB3 / 2; ++j)
+      res.v[i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq, 0) * K::C + lane_channel(chb, K::NB3, 2 * j, lg, 0));
+  }
+}
+
 // HOISTED: `ring` arrives holding steps 0 .. RD-1 and is left holding them again (the refills wrap around).
+// res0: the first pass's residual if the caller has requested it already (conv3_residual_request), else null.
 template <class K, int NB2, bool HOISTED>
 __device__ LASNET_PHASE_INLINE void conv3_core(Conv3Ring<K>& ring, g_bf16_p x, g_bf16_p W3, l_f32_cp b3s,
                                                l_i32_cp pixq, l_bf16_cp y2s, l_bf16_p tscratch,
-                                               AS_GLOBAL __bf16* out, int post_relu, int tid, int wave, int wc0 = 0) {
+                                               AS_GLOBAL __bf16* out, int post_relu, int tid, int wave, int wc0 = 0,
+                                               const Conv3Residual<K, NB2>* res0 = nullptr) {
   constexpr int C = K::C, NB = K::NB3, MS = K::MS, RD = K::RD3;
   constexpr int NPASS = K::NBT3 / NB, NSTEP = NPASS * MS;
   constexpr int RB = cdiv(NB2, K::WR3);
@@ -687,7 +704,14 @@ __device__ LASNET_PHASE_INLINE void conv3_core(Conv3Ring<K>& ring, g_bf16_p x, g
       for (int j = 0; j < NB / 2; ++j)   // rows past the last pixel read pixel 0 (never stored)
         xres[pass & 1][i][j] = *reinterpret_cast<const AS_GLOBAL bf16x8*>(x + (size_t)max(pq[i], 0) * C + lane_channel(chb, NB, 2 * j, lg, 0));
   };
-  rload(0);
+  if (res0) {
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB / 2; ++j) xres[0][i][j] = res0->v[i][j];
+  } else {
+    rload(0);
+  }
   // fully unrolled, like conv1 and conv2: the weight ring runs on across the passes
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
@@ -766,14 +790,6 @@ __device__ LASNET_PHASE_INLINE void conv3_core(Conv3Ring<K>& ring, g_bf16_p x, g
       }
     }
   }
-}
-
-template <class K, int NB2>
-__device__ LASNET_PHASE_INLINE void conv3_phase(g_bf16_p x, g_bf16_p W3, l_f32_cp b3s, l_i32_cp pixq,
-                                                l_bf16_cp y2s, l_bf16_p tscratch, AS_GLOBAL __bf16* out,
-                                                int post_relu, int tid, int wave) {
-  Conv3Ring<K> ring;
-  conv3_core<K, NB2, false>(ring, x, W3, b3s, pixq, y2s, tscratch, out, post_relu, tid, wave);
 }
 
 template <class K>
@@ -934,14 +950,23 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     });
     __syncthreads();
     constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
+    // conv2 and conv3 share one dispatch on the block count: conv3's first residual is requested at the
+    // start of conv2 and handed over in registers
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
-      conv2_phase<K, decltype(nb)::value * WR23>((g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s,
-                                                 (l_bf16_p)y2s, nq, opaque(tid), wave);
-    });
-    __syncthreads();
-    dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
-      conv3_phase<K, decltype(nb)::value * WR23>((g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq,
-                                                 (l_bf16_cp)y2s, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, opaque(tid), wave);
+      constexpr int NB2 = decltype(nb)::value * WR23;
+      // conv2's first weights are requested before the residual: a wave's loads complete in issue order,
+      // and these come from L2 while the residual comes from memory
+      Conv2Ring<K> ring2;
+      conv2_ring_fill<K>(ring2, (g_bf16_p)W2, opaque(tid), wave);
+      Conv3Residual<K, NB2> res;
+      conv3_residual_request<K, NB2>(res, (g_bf16_p)x, (l_i32_cp)pixq, opaque(tid), wave);
+      // (the ring arrives filled; the first k-steps it re-requests at the end are not used)
+      conv2_core<K, NB2, true>(ring2, (g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s, (l_bf16_p)y2s,
+                               nq, opaque(tid), wave);
+      __syncthreads();
+      Conv3Ring<K> ring3;
+      conv3_core<K, NB2, false>(ring3, (g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq, (l_bf16_cp)y2s,
+                                (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, opaque(tid), wave, 0, &res);
     });
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch

@@ -20,7 +20,7 @@
 // group's cells; the result does not depend on the list's order) and leaves it in the workspace for
 // T2 and T3, which derive the same ascending pixel order from it.
 //
-// The GEMM cores are the fused kernel's phases (conv1_phase / conv2_phase / conv3_phase), here with
+// The GEMM cores are the fused kernel's phases (conv1_core / conv2_core / conv3_core), here with
 // one wave per SIMD and 4 channel tiles per wave where the shape allows: D[channel][pixel] with
 // v_mfma_f32_16x16x32_bf16, activations from LDS, weights as prepacked A-fragments from L2.
 #pragma once
