@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kMaskerThreads) void masker_logit_kernel(
   }
 }
 
-// The common case (a patch row is exactly 4 KiB, S in {2, 4, 8}: every ResNet stage in bf16) with the
+// The common case (a patch row is exactly 4 KiB, S in {1, 2, 4, 8}: every ResNet stage in bf16) with the
 // cell split by rows over WPC waves of the workgroup: a wave takes two rows (8 KiB, eight 16-byte
 // pieces per lane), keeps them in registers, and the waves of a cell add their partial sums in a
 // fixed order through LDS.  An inactive cell is then written to pass_out from those registers: x is
@@ -331,14 +331,16 @@ hipError_t launch_masker(const lasnet_tensor& x, const float* Wm, float bm, int 
                      mask, logits, (T*)pass_out)
   if (P == 0) {
     // empty batch: nothing to pool; the compaction below still writes count = 0
-  } else if (hoist && (S == 2 || S == 4 || S == 8)) {
+  } else if (hoist && (S == 1 || S == 2 || S == 4 || S == 8)) {
     if (x.dtype == LASNET_BF16) {
-      if (S == 2) LASNET_MASKER_ROWS(uint16_t, 2, 1);      // one row per wave: 0.9 us faster than two at stage 3
+      if (S == 1) LASNET_MASKER_ROWS(uint16_t, 1, 1);      // pixel-level cells (7x7x2048): a cell is one row
+      else if (S == 2) LASNET_MASKER_ROWS(uint16_t, 2, 1); // one row per wave: 0.9 us faster than two at stage 3
       else if (S == 4 && pass_out) LASNET_MASKER_ROWS(uint16_t, 4, 1);   // with the pass-through: 1.3 us faster
       else if (S == 4) LASNET_MASKER_ROWS(uint16_t, 2);                  // without: 0.7 us faster
       else LASNET_MASKER_ROWS(uint16_t, 4);
     } else {
-      if (S == 2) LASNET_MASKER_ROWS(float, 2, 1);
+      if (S == 1) LASNET_MASKER_ROWS(float, 1, 1);
+      else if (S == 2) LASNET_MASKER_ROWS(float, 2, 1);
       else if (S == 4) LASNET_MASKER_ROWS(float, 2);
       else LASNET_MASKER_ROWS(float, 4);
     }

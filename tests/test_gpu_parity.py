@@ -46,7 +46,8 @@ MASKER_CASES = [
     synth.BlockConfig("odd_c20_s1_bf16", 2, 5, 7, 20, 12, 1, "bf16", 0.3, 22),
     synth.BlockConfig("pixel_s1_manycells", 8, 32, 32, 8, 8, 1, "f32", 0.37, 23),  # P = 8192: 8 compaction rounds
     synth.BlockConfig("layer_skip_sH", 3, 8, 8, 16, 8, 8, "bf16", 0.34, 24),       # S = H: one cell per image
-    # fp32 with 4 KiB patch rows: the row-split masker with 1, 2 and 4 waves per cell, odd cell counts
+    # fp32 with 4 KiB patch rows: the row-split masker with 1, 2 and 4 waves per cell (S = 1: one row per cell), odd cell counts
+    synth.BlockConfig("rows_f32_s1", 1, 5, 7, 1024, 16, 1, "f32", 0.45, 31),
     synth.BlockConfig("rows_f32_s2", 1, 6, 6, 512, 16, 2, "f32", 0.45, 28),
     synth.BlockConfig("rows_f32_s4", 1, 12, 12, 256, 16, 4, "f32", 0.45, 29),
     synth.BlockConfig("rows_f32_s8", 3, 8, 24, 128, 16, 8, "f32", 0.45, 30),
