@@ -156,10 +156,24 @@ def main():
     copy_ms = timed_loop(lambda i: B.lasnet_microbench_copy(cp_src, cp_dst), 10)
     sustained_gbs = 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9
     del cp_src, cp_dst
+    # every CU reading the same 2.25 MiB (the size of the 14x14x1024 block's weights) from L2, as the block kernels do
+    ws_buf = torch.zeros(18 * 128 * 1024, dtype=torch.uint8, device=dev)
+    ws_box = [0.0]
+
+    def ws_loop(i):
+        ws_box[0] = B.lasnet_microbench_weight_stream(ws_buf, 20, sink)
+
+    ws_ms = timed_loop(ws_loop, 10)
+    ws_gbs = ws_box[0] / (ws_ms * 1e-3) / 1e9
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     achievable = {"mfma_bf16_tflops": sustained_tflops, "mfma_frac_of_nominal": sustained_tflops / PEAK_BF16_TFLOPS,
                   "stream_copy_gbs": sustained_gbs, "copy_frac_of_nominal": sustained_gbs / PEAK_HBM_GBS,
+                  "weight_stream_gbs": ws_gbs, "weight_stream_gbs_per_cu": ws_gbs / n_cu,
+                  "weight_stream_us_per_pass_of_2.25MiB": ws_buf.numel() / (ws_gbs / n_cu * 1e9) * 1e6,
                   "note": "register-only v_mfma_f32_16x16x32_bf16 loop on every SIMD (4 waves each, 16 independent "
-                          "accumulators); out = in over 512 MiB with 16 bytes per lane (read + written bytes counted)"}
+                          "accumulators); out = in over 512 MiB with 16 bytes per lane (read + written bytes counted); "
+                          "one 8-wave workgroup per CU, all reading the same 2.25 MiB from L2 in 1 KiB wave-wide pieces, "
+                          "16 loads per lane in flight (what a CU's weight stream can reach when every CU streams)"}
 
     # ------------------------------------------------------------------ one workload
     def load(cfg):

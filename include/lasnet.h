@@ -274,8 +274,15 @@ LASNET_API int lasnet_has_fast_path(int dtype, int C, int M, int S);
  *                            error.  sink: any device buffer of at least 2 KiB (never written).
  *   lasnet_microbench_copy   out = in with the library's copy kernel; bytes a multiple of 16, both
  *                            pointers 16-byte aligned (else LASNET_EINVAL).
+ *   lasnet_microbench_weight_stream
+ *                            one 8-wave workgroup per CU, each reading buf[0 .. bytes) `passes` times in
+ *                            wave-wide 1 KiB pieces, as the block kernels read their packed weights (every CU
+ *                            the same lines at the same time); bytes a multiple of 128 KiB, at most 1 GiB, buf
+ *                            16-byte aligned; returns the bytes read over all CUs, 0 on error.  sink as above.
  */
 LASNET_API double lasnet_microbench_mfma(int iters, void* sink, void* hip_stream);
+LASNET_API double lasnet_microbench_weight_stream(const void* buf, size_t bytes, int passes, void* sink,
+                                                  void* hip_stream);
 LASNET_API int lasnet_microbench_copy(const void* in, void* out, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus

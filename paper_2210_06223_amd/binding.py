@@ -28,7 +28,7 @@ EXPORTS = (
     "lasnet_has_fast_path", "lasnet_packed_weights_bytes", "lasnet_pack_weights",
     "lasnet_sparse_bottleneck_packed", "lasnet_sparse_bottleneck_noalloc",
     "lasnet_workspace_bytes", "lasnet_sparse_bottleneck_planned",
-    "lasnet_microbench_mfma", "lasnet_microbench_copy",
+    "lasnet_microbench_mfma", "lasnet_microbench_copy", "lasnet_microbench_weight_stream",
 )
 
 
@@ -74,6 +74,8 @@ def load_library(path: str) -> ctypes.CDLL:
                                                    vp, ctypes.c_size_t, vp]
     L.lasnet_microbench_mfma.restype = ctypes.c_double
     L.lasnet_microbench_mfma.argtypes = [ip, vp, vp]
+    L.lasnet_microbench_weight_stream.restype = ctypes.c_double
+    L.lasnet_microbench_weight_stream.argtypes = [vp, ctypes.c_size_t, ip, vp, vp]
     L.lasnet_microbench_copy.restype = ip
     L.lasnet_microbench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.lasnet_sparse_bottleneck_noalloc.restype = ip
@@ -353,6 +355,15 @@ def lasnet_microbench_mfma(iters: int, sink: torch.Tensor, stream=None) -> float
     f = lib().lasnet_microbench_mfma(int(iters), _ptr(sink), _stream(stream))
     if f <= 0:
         raise LasnetError(LASNET_EHIP, "lasnet_microbench_mfma")
+    return float(f)
+
+
+def lasnet_microbench_weight_stream(buf: torch.Tensor, passes: int, sink: torch.Tensor, stream=None) -> float:
+    """Every CU reads `buf` `passes` times the way the block kernels read their weights; returns the bytes read."""
+    f = lib().lasnet_microbench_weight_stream(_ptr(buf), buf.numel() * buf.element_size(), int(passes), _ptr(sink),
+                                              _stream(stream))
+    if f <= 0:
+        raise LasnetError(LASNET_EHIP, "lasnet_microbench_weight_stream")
     return float(f)
 
 
