@@ -156,3 +156,18 @@ def test_schedules_workspace_query_and_planned_entry_argument_errors():
     st = L.lasnet_sparse_bottleneck_noalloc(ctypes.byref(x), p, p, 2, 256, p, p, p, p, p, p, ctypes.byref(o),
                                             B.LASNET_FORCE_TILED, None)
     assert st == B.LASNET_EUNSUPPORTED                                         # that entry never runs the tiled schedule
+
+
+def test_microbenchmark_argument_errors():
+    """Bad arguments are refused on the host (0 FLOPs / 0 bytes / LASNET_EINVAL) before any HIP call."""
+    L = B.lib()
+    vp = ctypes.c_void_p
+    assert L.lasnet_microbench_mfma(0, vp(0x1000), None) == 0.0
+    assert L.lasnet_microbench_mfma(10, None, None) == 0.0
+    assert L.lasnet_microbench_weight_stream(None, 128 * 1024, 1, vp(0x1000), None) == 0.0
+    assert L.lasnet_microbench_weight_stream(vp(0x1000), 100 * 1024, 1, vp(0x1000), None) == 0.0      # not whole 128 KiB
+    assert L.lasnet_microbench_weight_stream(vp(0x1008), 128 * 1024, 1, vp(0x1000), None) == 0.0      # misaligned
+    assert L.lasnet_microbench_weight_stream(vp(0x1000), 128 * 1024, 0, vp(0x1000), None) == 0.0
+    assert L.lasnet_microbench_weight_stream(vp(0x1000), 2 << 30, 1, vp(0x1000), None) == 0.0          # beyond 1 GiB
+    assert L.lasnet_microbench_copy(vp(0x1000), vp(0x2000), 24, None) == B.LASNET_EINVAL
+    assert L.lasnet_microbench_copy(vp(0x1004), vp(0x2000), 32, None) == B.LASNET_EINVAL
