@@ -304,12 +304,18 @@ __device__ __forceinline__ void conv1_ring_fill(Conv1Ring<K>& ring, g_bf16_p W1,
       ring.w[t][j] = buf_load16(wrs, lane16 + j * 1024, wbase + t * K::W_KSTEP_BYTES);
 }
 
+// What conv1 runs between requesting its first chunks and waiting for them, when the caller has nothing to put there.
+struct Nothing { __device__ __forceinline__ void operator()() const {} };
+
 // HOISTED: `ring` arrives filled by conv1_ring_fill.  yg / nrows: with K::Y1_TO_GLOBAL the result rows
-// go straight to memory, row r < nrows to yg + rowpix[r] * K::YG_PITCH (+ channel).
-template <class K, int NB1, bool HOISTED>
+// go straight to memory, row r < nrows to yg + rowpix[r] * K::YG_PITCH (+ channel).  `meanwhile` runs after
+// the first chunks of x and weights have been requested and before the first of them is waited for: work
+// that needs no global memory hides behind that latency (it must not touch xs or y1s).
+template <class K, int NB1, bool HOISTED, class Meanwhile = Nothing>
 __device__ LASNET_PHASE_INLINE void conv1_core(Conv1Ring<K>& ring, g_bf16_p x, g_bf16_p W1, l_f32_cp b1s,
                                                l_i32_cp rowpix, l_bf16_p xs, l_bf16_p y1s, int tid, int wave,
-                                               AS_GLOBAL __bf16* yg = nullptr, int nrows = 0) {
+                                               AS_GLOBAL __bf16* yg = nullptr, int nrows = 0,
+                                               Meanwhile meanwhile = Meanwhile{}) {
   constexpr int C = K::C, NBW = K::NBW1, KS = K::KC / 32, NCH = C / K::KC;
   constexpr int RB = cdiv(NB1, K::WR1);                   // row blocks of this wave (last may be padding)
   constexpr int NGRP = NB1 * 2, NXL = cdiv(NGRP, K::NW);  // 8-row groups; x loads per wave per chunk
@@ -394,6 +400,9 @@ __device__ LASNET_PHASE_INLINE void conv1_core(Conv1Ring<K>& ring, g_bf16_p x, g
     }
   }
 
+  meanwhile();
+  __builtin_amdgcn_sched_barrier(0);
+
   // B fragments are read one k-step ahead of the MFMAs that use them (bcur/bnxt), so a
   // wave's LDS latency hides behind its own matrix work.
   bf16x8 bcur[RB], bnxt[RB];
@@ -464,11 +473,12 @@ __device__ LASNET_PHASE_INLINE void conv1_core(Conv1Ring<K>& ring, g_bf16_p x, g
   }
 }
 
-template <class K, int NB1>
+template <class K, int NB1, class Meanwhile = Nothing>
 __device__ LASNET_PHASE_INLINE void conv1_phase(g_bf16_p x, g_bf16_p W1, l_f32_cp b1s, l_i32_cp rowpix,
-                                                l_bf16_p xs, l_bf16_p y1s, int tid, int wave) {
+                                                l_bf16_p xs, l_bf16_p y1s, int tid, int wave,
+                                                Meanwhile meanwhile = Meanwhile{}) {
   Conv1Ring<K> ring;
-  conv1_core<K, NB1, false>(ring, x, W1, b1s, rowpix, xs, y1s, tid, wave);
+  conv1_core<K, NB1, false>(ring, x, W1, b1s, rowpix, xs, y1s, tid, wave, nullptr, 0, meanwhile);
 }
 
 // ---- phase 2: conv3x3 as an implicit GEMM over the 9 taps, y1 rows from LDS ---------------
@@ -908,45 +918,47 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     }
     const int nblk1 = max(1, (U + 15) >> 4);              // (U = 0 only if every entry of the batch was invalid)
     const int nq = npb * S * S, nblk2 = (nq + 15) >> 4;
-    // (c) row of every window position; pixel of every output row
-    for (int t = tid; t < npb * WW; t += K::NT) {
-      const int slot = t / WW, wp = t - slot * WW;
-      const int cell = cellq[slot];
-      const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
-      const int gy = rem / g.GW, gx = rem - gy * g.GW;
-      const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
-      int row = K::ZROW;
-      if ((unsigned)cell < (unsigned)g.P && h >= 0 && h < g.H && w >= 0 && w < g.W) {
-        const int key = (n * g.H + h) * g.W + w + 1;
-        unsigned s = hash_pix(key) & (K::HT - 1);
-        while (hkey[s] != key) s = (s + 1) & (K::HT - 1);
-        row = hval[s];
-      }
-      winrow[t] = (short)row;
-    }
-    __syncthreads();                                       // rowpix[0] is final
     // rows up to the block count conv1 really runs (rounded up to its wave rows) must name
     // a valid pixel: their x is loaded and convolved, the result is never used
     const int pad_pix = U > 0 ? rowpix[0] : 0;
     for (int r = U + tid; r < (nblk1 + K::WR1 - 1) / K::WR1 * K::WR1 * 16; r += K::NT) rowpix[r] = pad_pix;
-    for (int q = tid; q < K::R2P; q += K::NT) {
-      int pix = -1;
-      if (q < nq) {
-        const int slot = q / (S * S), r = q - slot * (S * S);
+    __syncthreads();
+    // (c) row of every window position; pixel of every output row.  Only conv2 and conv3 need these, so
+    // they are built inside conv1, between the request for its first chunks of x and the wait for them.
+    const auto tables = [&] {
+      for (int t = tid; t < npb * WW; t += K::NT) {
+        const int slot = t / WW, wp = t - slot * WW;
         const int cell = cellq[slot];
         const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
         const int gy = rem / g.GW, gx = rem - gy * g.GW;
-        if ((unsigned)cell < (unsigned)g.P) pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
+        const int h = gy * S + wp / T - 1, w = gx * S + wp % T - 1;
+        int row = K::ZROW;
+        if ((unsigned)cell < (unsigned)g.P && h >= 0 && h < g.H && w >= 0 && w < g.W) {
+          const int key = (n * g.H + h) * g.W + w + 1;
+          unsigned s = hash_pix(key) & (K::HT - 1);
+          while (hkey[s] != key) s = (s + 1) & (K::HT - 1);
+          row = hval[s];
+        }
+        winrow[t] = (short)row;
       }
-      pixq[q] = pix;
-    }
-    __syncthreads();
+      for (int q = tid; q < K::R2P; q += K::NT) {
+        int pix = -1;
+        if (q < nq) {
+          const int slot = q / (S * S), r = q - slot * (S * S);
+          const int cell = cellq[slot];
+          const int n = cell / (g.G * g.GW), rem = cell - n * (g.G * g.GW);
+          const int gy = rem / g.GW, gx = rem - gy * g.GW;
+          if ((unsigned)cell < (unsigned)g.P) pix = (n * g.H + gy * S + r / S) * g.W + gx * S + r % S;
+        }
+        pixq[q] = pix;
+      }
+    };
 
     // Row blocks are dealt to the wave rows round-robin (wave row wr takes blocks wr, wr+WR,
     // ...); the count is rounded up to a multiple of WR, the extra blocks compute unused rows.
     dispatch_count<1, K::R1B / K::WR1>((nblk1 + K::WR1 - 1) / K::WR1, [&](auto nb) {
       conv1_phase<K, decltype(nb)::value * K::WR1>((g_bf16_p)x, (g_bf16_p)W1, (l_f32_cp)b1s, (l_i32_cp)rowpix,
-                                                   (l_bf16_p)xs, (l_bf16_p)y1s, opaque(tid), wave);
+                                                   (l_bf16_p)xs, (l_bf16_p)y1s, opaque(tid), wave, tables);
     });
     __syncthreads();
     constexpr int WR23 = K::WR2 > K::WR3 ? K::WR2 : K::WR3;
