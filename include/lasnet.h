@@ -131,6 +131,9 @@ LASNET_API int lasnet_masker_logits(const lasnet_tensor* x, const float* Wm, flo
  * idx; entries must be unique (not checked).  An entry that is not a cell of this map
  * (negative, or >= N*G*GW) is ignored; a count[0] beyond N*G*GW is read as N*G*GW.
  * idx == NULL means "all cells active" and count is then ignored (may be NULL).
+ * The list's STORAGE must have room for N*G*GW entries, as the buffer lasnet_masker fills has: the count is
+ * known only on the device, and the kernels may read (never use) entries past count[0] -- they request the
+ * list together with the count instead of after it.  A caller that builds its own list pads the buffer.
  *
  * M: bottleneck width.  out: same shape and dtype as x.  Normally a different buffer: in the fused
  * schedule a patch updated in place would corrupt the neighbour read of an adjacent active

@@ -220,6 +220,18 @@ def _weights(x, W1, b1, W2, b2, W3, b3):
                     _ptr(_f32(b3, "b3"))]
 
 
+def _check_list(x: torch.Tensor, idx: Optional[torch.Tensor], count: Optional[torch.Tensor], S: int) -> None:
+    """The list's storage is what the masker writes to: room for every cell of the map (the kernels may read
+    entries past count[0], which only the device knows; they never use them)."""
+    for n, t in (("idx", idx), ("count", count)):
+        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    if idx is not None and int(S) > 0 and x.dim() == 4 and x.shape[1] % int(S) == 0 and x.shape[2] % int(S) == 0:
+        cells = int(x.shape[0]) * (int(x.shape[1]) // int(S)) * (int(x.shape[2]) // int(S))
+        if idx.numel() < cells:
+            raise ValueError("idx must have room for all %d cells of the map (it holds %d entries)" % (cells, idx.numel()))
+
+
 def lasnet_sparse_bottleneck(x: torch.Tensor, idx: Optional[torch.Tensor],
                              count: Optional[torch.Tensor], S: int, W1, b1, W2, b2, W3, b3,
                              out: Optional[torch.Tensor] = None, flags: int = 0,
@@ -229,9 +241,7 @@ def lasnet_sparse_bottleneck(x: torch.Tensor, idx: Optional[torch.Tensor],
         out = torch.empty_like(x)
     o = _as_tensor_desc(out)
     M, w = _weights(x, W1, b1, W2, b2, W3, b3)
-    for n, t in (("idx", idx), ("count", count)):
-        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
-            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    _check_list(x, idx, count, S)
     if flags:
         st = lib().lasnet_sparse_bottleneck_ex(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), M, *w,
                                                ctypes.byref(o), int(flags), _stream(stream))
@@ -256,9 +266,7 @@ def lasnet_sparse_bottleneck_planned(x: torch.Tensor, idx: Optional[torch.Tensor
     """The explicit form: packed weights, workspace (a uint8 device tensor or None) and out are the caller's."""
     d = _as_tensor_desc(x)
     o = _as_tensor_desc(out)
-    for n, t in (("idx", idx), ("count", count)):
-        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
-            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    _check_list(x, idx, count, S)
     if mask is not None and (mask.dtype != torch.uint8 or not mask.is_cuda or not mask.is_contiguous()):
         raise ValueError("mask must be a contiguous uint8 device tensor")
     if b1.numel() != M or b2.numel() != M or b3.numel() != x.shape[3]:
@@ -280,9 +288,7 @@ def lasnet_sparse_bottleneck_noalloc(x: torch.Tensor, idx: Optional[torch.Tensor
     d = _as_tensor_desc(x)
     o = _as_tensor_desc(out)
     M, w = _weights(x, W1, b1, W2, b2, W3, b3)
-    for n, t in (("idx", idx), ("count", count)):
-        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
-            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    _check_list(x, idx, count, S)
     st = lib().lasnet_sparse_bottleneck_noalloc(ctypes.byref(d), _ptr(idx), _ptr(count), int(S), M, *w,
                                                 ctypes.byref(o), int(flags), _stream(stream))
     _check(st, "lasnet_sparse_bottleneck_noalloc")
@@ -334,9 +340,7 @@ def lasnet_sparse_bottleneck_packed(x: torch.Tensor, idx: Optional[torch.Tensor]
     if out is None:
         out = torch.empty_like(x)
     o = _as_tensor_desc(out)
-    for n, t in (("idx", idx), ("count", count)):
-        if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
-            raise ValueError("%s must be a contiguous int32 device tensor" % n)
+    _check_list(x, idx, count, S)
     need = lib().lasnet_packed_weights_bytes(LASNET_BF16, int(x.shape[3]), int(M), int(S))
     if need and packed.numel() * packed.element_size() < need:
         raise ValueError("packed buffer too small for this shape")

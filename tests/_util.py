@@ -76,3 +76,11 @@ def assert_block_close(got: torch.Tensor, ref: np.ndarray, x: torch.Tensor, up_m
         assert float(err.max()) <= rtol * float(np.abs(ra).max()), what + ": max-norm error"
         rel_l2 = float(np.sqrt(np.sum(err * err) / max(np.sum(ra * ra), 1e-300)))
         assert rel_l2 <= rtol, "%s: relative L2 error %.3g > %.3g" % (what, rel_l2, rtol)
+
+
+def list_tensor(entries: np.ndarray, P: int) -> torch.Tensor:
+    """An index list in storage of the size the masker writes to: P entries, the unused tail poisoned."""
+    t = torch.full((max(int(P), 1),), -7, dtype=torch.int32, device="cuda")
+    if len(entries):
+        t[: len(entries)] = torch.from_numpy(np.asarray(entries, np.int32)).cuda()
+    return t

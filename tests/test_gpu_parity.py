@@ -278,7 +278,7 @@ def test_prepacked_weights_entry_point_matches_plain_one():
     inp = synth.make_block_inputs(cfg)
     d = U.dev_inputs(inp)
     il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=11)
-    idx = torch.from_numpy(il).cuda()
+    idx = U.list_tensor(il, cfg.P)
     count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
     a = B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d))
     packed = B.lasnet_pack_weights(cfg.S, d["W1"], d["W2"], d["W3"])
@@ -335,7 +335,7 @@ def test_skip_identity_flag_leaves_inactive_untouched():
     inp = synth.make_block_inputs(cfg)
     d = U.dev_inputs(inp)
     idx_np = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.4, seed=9)
-    idx = torch.from_numpy(idx_np).cuda()
+    idx = U.list_tensor(idx_np, cfg.P)
     count = torch.tensor([len(idx_np)], dtype=torch.int32, device="cuda")
     out = torch.full_like(d["x"], 5.0)
     B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), out=out,
@@ -358,6 +358,9 @@ def test_errors_on_device_tensors():
     with pytest.raises(B.LasnetError) as e:
         B.lasnet_sparse_bottleneck(d["x"], idx, count, 3, *U.weights(d))
     assert e.value.status == B.LASNET_ESHAPE
+    # the list's storage must have room for every cell (the kernels request it together with the count)
+    with pytest.raises(ValueError):
+        B.lasnet_sparse_bottleneck(d["x"], idx[: cfg.P - 1].contiguous(), count, cfg.S, *U.weights(d))
 
 
 # ------------------------------------------------------------------ full size, as bench.py launches it
@@ -449,7 +452,7 @@ def test_count_beyond_capacity_and_invalid_entries(cfg):
     assert len(good) < len(mixed) <= cfg.P
     mask = np.zeros(cfg.P, np.uint8); mask[good] = 1
     mask = mask.reshape(cfg.N, cfg.G, cfg.GW)
-    idx = torch.from_numpy(mixed).cuda()
+    idx = U.list_tensor(mixed, cfg.P)
     count = torch.tensor([len(mixed)], dtype=torch.int32, device="cuda")
     out = torch.full_like(d["x"], 777.0)
     B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *w, out=out)
@@ -505,7 +508,7 @@ def test_check_build_with_drained_barriers_is_bit_identical(monkeypatch):
         inp = synth.make_block_inputs(cfg)
         d = U.dev_inputs(inp)
         il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, k / cfg.P, seed=cfg.seed + 1000)
-        idx = torch.from_numpy(il).cuda() if len(il) else torch.zeros(1, dtype=torch.int32, device="cuda")
+        idx = U.list_tensor(il, cfg.P)
         count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
         for flags in ((B.LASNET_FORCE_FUSED, B.LASNET_FORCE_TILED) if _tiled(cfg) else (0,)):
             outs = []
@@ -575,7 +578,7 @@ def test_in_place_update_on_the_tiled_schedule(cfg, flags):
     inp = synth.make_block_inputs(cfg)
     d = U.dev_inputs(inp)
     il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=cfg.seed + 3)
-    idx = torch.from_numpy(il).cuda()
+    idx = U.list_tensor(il, cfg.P)
     count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
     for post in (0, B.LASNET_POST_RELU):
         want = B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), flags=flags | post)

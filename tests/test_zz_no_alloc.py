@@ -38,7 +38,7 @@ def test_noalloc_entry_matches_the_allocating_one_twice_in_a_row():
         inp = synth.make_block_inputs(cfg)
         d = U.dev_inputs(inp)
         il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.5, seed=cfg.seed + 7)
-        idx = torch.from_numpy(il).cuda()
+        idx = U.list_tensor(il, cfg.P)
         count = torch.tensor([len(il)], dtype=torch.int32, device="cuda")
         want = d["x"].clone()
         B.lasnet_sparse_bottleneck(d["x"], idx, count, cfg.S, *U.weights(d), out=want, flags=flags)
