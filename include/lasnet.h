@@ -169,9 +169,8 @@ LASNET_API int lasnet_sparse_bottleneck_ex(const lasnet_tensor* x, const int32_t
  *          y2 passing through a workspace in device memory.  Built for 1024x256 channels on maps of
  *          up to 196 pixels (14x14) and 2048x512 channels on maps of up to 49 pixels (7x7), any patch
  *          size.  The library's own choice for 2048x512 (measured faster there at every activation
- *          rate); for 1024x256 the fused kernel measured faster below an activation rate of about 0.75
- *          and the same above, so the tiled one runs only with LASNET_FORCE_TILED (a caller that
- *          knows its rate is high, or that wants the in-place update).
+ *          rate); for 1024x256 the fused kernel measured faster or equal at every rate, so the tiled
+ *          one runs only with LASNET_FORCE_TILED (a caller that wants the in-place update).
  * Results are the same function of the inputs either way (same roundings: y1, y2 to bf16, out once).
  * The tiled schedule needs lasnet_workspace_bytes() of device memory (that query answers for every
  * shape that has a tiled schedule, chosen by default or not; 0 = none): lasnet_sparse_bottleneck[_ex],

@@ -60,6 +60,7 @@ struct Cfg {
   static constexpr int WR3 = WR3_, WC3 = WC3_, NBT3 = C / 16 / WC3, NB3 = NB3_, RD3 = RD3_;
   static constexpr int R2 = PPW * S * S;
   static constexpr int R2B = roundup(cdiv(R2, 16), cmax(WR2, WR3)), R2P = R2B * 16;
+  static constexpr int NB3ROWS = 4 * WR3;              // row blocks conv3 takes at a time
   // LDS rows have power-of-two pitch and their 16-byte chunks are XOR-swizzled (see swz()):
   // measured on gfx950, ds_read_b128 then runs at ~6 clk per wave against ~9 with a padded pitch.
   static constexpr int LDX = KC, LDY = M;
@@ -966,19 +967,30 @@ __global__ __launch_bounds__(K::NT, K::WAVES_PER_SIMD) void fused_bneck_kernel(
     // start of conv2 and handed over in registers
     dispatch_count<1, K::R2B / WR23>((nblk2 + WR23 - 1) / WR23, [&](auto nb) {
       constexpr int NB2 = decltype(nb)::value * WR23;
+      // conv3 keeps a row block's whole output line in registers: it takes the batch's rows in groups of at most
+      // NB3ROWS blocks (its weights stream again for the second group; a second batch would stream all three)
+      constexpr int NB3A = NB2 < K::NB3ROWS ? NB2 : K::NB3ROWS, NB3B = NB2 - NB3A;
+      static_assert(NB3B <= K::NB3ROWS && (NB3B == 0 || (NB3A * 16) % 16 == 0), "two groups of row blocks at most");
       // conv2's first weights are requested before the residual: a wave's loads complete in issue order,
       // and these come from L2 while the residual comes from memory
       Conv2Ring<K> ring2;
       conv2_ring_fill<K>(ring2, (g_bf16_p)W2, opaque(tid), wave);
-      Conv3Residual<K, NB2> res;
-      conv3_residual_request<K, NB2>(res, (g_bf16_p)x, (l_i32_cp)pixq, opaque(tid), wave);
+      Conv3Residual<K, NB3A> res;
+      conv3_residual_request<K, NB3A>(res, (g_bf16_p)x, (l_i32_cp)pixq, opaque(tid), wave);
       // (the ring arrives filled; the first k-steps it re-requests at the end are not used)
       conv2_core<K, NB2, true>(ring2, (g_bf16_p)W2, (l_f32_cp)b2s, (l_i16_cp)winrow, (l_bf16_cp)y1s, (l_bf16_p)y2s,
                                nq, opaque(tid), wave);
       __syncthreads();
       Conv3Ring<K> ring3;
-      conv3_core<K, NB2, false>(ring3, (g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq, (l_bf16_cp)y2s,
-                                (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, opaque(tid), wave, 0, &res);
+      conv3_core<K, NB3A, false>(ring3, (g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq, (l_bf16_cp)y2s,
+                                 (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu, opaque(tid), wave, 0, &res);
+      if constexpr (NB3B > 0) {
+        // rows NB3A*16 ..: a whole number of swizzle periods further on, so the row keys conv2 wrote them with still fit
+        Conv3Ring<K> ring3b;
+        conv3_core<K, NB3B, false>(ring3b, (g_bf16_p)x, (g_bf16_p)W3, (l_f32_cp)b3s, (l_i32_cp)pixq + NB3A * 16,
+                                   (l_bf16_cp)y2s + NB3A * 16 * K::LDY, (l_bf16_p)y1s, (AS_GLOBAL __bf16*)out, post_relu,
+                                   opaque(tid), wave);
+      }
     });
     e0 += npb;
     if (e0 < te) __syncthreads();                          // LDS is reused by the next batch

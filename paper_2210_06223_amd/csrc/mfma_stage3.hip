@@ -4,12 +4,13 @@
 namespace lasnet {
 namespace {
 //             C     M   S PPW R1MAX NW KC NSTG conv1  conv2 RD2  conv3 NB3 RD3
-// Weights are 2.2 MB: one 8-wave workgroup per CU with up to 16 patches (64 pixels at S=1), so that
-// the weights stream through a CU once per batch.
-// (weight rings of 4 and 2 steps: deeper ones cost registers, and spills inside the k-loops
-// cost more than the extra latency cover is worth -- measured 46 us against 49)
-using K_s3 = Cfg<1024, 256, 2, 16, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // S=2
-using K_s3s7 = Cfg<1024, 256, 7, 1, 96, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // S=7 (also the dense tile)
+// Weights are 2.2 MB: one 8-wave workgroup per CU whose batch is as large as LDS allows -- up to 32 patches at
+// S=2 (128 output rows; what bounds it in practice is the 160 y1 rows of distinct window pixels), two tiles at
+// S=7 (side by side they share a window column: 144 rows) -- so that the weights stream through a CU once
+// for everything the CU has to do, up to an activation ratio of 1 at batch 128.
+// (weight rings of 4 and 2 steps: deeper ones measured the same)
+using K_s3 = Cfg<1024, 256, 2, 32, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;    // S=2
+using K_s3s7 = Cfg<1024, 256, 7, 2, 144, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;   // S=7 (also the dense tile)
 using K_s3s1 = Cfg<1024, 256, 1, 64, 160, 8, 64, 3, 1, 8, 1, 8, 4, 1, 8, 4, 2>;  // S=1 (pixel level)
 }  // namespace
 

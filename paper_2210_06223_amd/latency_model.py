@@ -10,6 +10,8 @@ to measured latency-against-ratio sweeps (profiles/ratio_sweeps_mi355x.txt):
 
   fused / streaming kernels   a workgroup's time = sum over its batches of
                                   a + b * (16-row blocks of conv1) + c * (16-row blocks of conv2/conv3)
+                                  (+ d when the batch has more than 4 output blocks: conv3 then takes its rows
+                                  in two groups and streams its weights twice)
                               a: what a batch costs whatever it holds (all weights stream through the CU,
                               the window set is built, pipelines fill); b, c: matrix work and activations.
                               Workgroups fill the chip's slots in launch order; latency = t0 + makespan.
@@ -34,7 +36,7 @@ N_CU = 256
 FUSED = {
     (256, 64, 8): dict(kind="stream"),
     (512, 128, 4): dict(kind="fused", PPW=4, R1MAX=112, wg_per_cu=2),
-    (1024, 256, 2): dict(kind="fused", PPW=16, R1MAX=160, wg_per_cu=1),
+    (1024, 256, 2): dict(kind="fused", PPW=32, R1MAX=160, wg_per_cu=1),
     (2048, 512, 1): dict(kind="fused", PPW=16, R1MAX=96, wg_per_cu=1),
 }
 TILED = {(1024, 256): dict(IMGS=1, T1ROWS=112, C2ROWS=128, C3ROWS=112), (2048, 512): dict(IMGS=2, T1ROWS=112, C2ROWS=128, C3ROWS=112)}
@@ -163,7 +165,8 @@ def _predict(f: dict, k: Dict[str, float], schedule: str, kind: str) -> float:
         return k["F"] + k["g1"] * f["nb1"] + k["g2"] * (f["nb2"] + f["nb3"]) + k["p"] * (f["np2"] + f["np3"] - 2)
     if kind == "stream":
         return k["t0"] + k["c"] * f["maxrun"]
-    times = [k["w0"] + sum(k["a"] + k["b"] * b1 + k["c"] * b2 for b1, b2 in wg) for wg in f["wgs"]]
+    times = [k["w0"] + sum(k["a"] + k["b"] * b1 + k["c"] * b2 + (k.get("d", 0.0) if b2 > 4 else 0.0) for b1, b2 in wg)
+             for wg in f["wgs"]]
     return k["t0"] + _makespan(times, f["slots"])
 
 
@@ -196,6 +199,8 @@ def fit(points: List[dict]) -> Dict[str, Dict[str, float]]:
         feats = [features(np.asarray(p["idx"]), p["N"], p["H"], p["W"], p["C"], p["M"], p["S"], sch) for p in pts]
         y = np.array([p["ms"] * 1e3 for p in pts])
         names = ["F", "g1", "g2", "p"] if sch == "tiled" else ["t0", "c"] if kind == "stream" else ["t0", "w0", "a", "b", "c"]
+        if sch != "tiled" and kind == "fused" and FUSED[(pts[0]["C"], pts[0]["M"], pts[0]["S"])]["PPW"] * pts[0]["S"] ** 2 > 64:
+            names.append("d")
         x0 = np.full(len(names), 1.0)
 
         def resid(v):
