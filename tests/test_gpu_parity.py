@@ -307,6 +307,22 @@ def test_all_active_null_index_list_equals_dense_oracle():
     U.assert_block_close(out, ref, d["x"], np.ones(ref.shape, bool), cfg.dtype, cfg.name)
 
 
+def test_full_batches_of_the_largest_size():
+    """More cells than 256 workgroups x 24: runs of 29-31 patches, i.e. batches of 8 output row blocks
+    (conv3 over two row groups), which batch 128 never reaches.  Every cell active, as a list and as NULL."""
+    cfg = _cfg("stage3_b128", N=160, name="s3_n160_all_active")
+    out_list = _run_case(cfg, idx_np=np.arange(cfg.P, dtype=np.int32), use_masker=False)
+    inp = synth.make_block_inputs(cfg)
+    d = U.dev_inputs(inp)
+    out_null = torch.full_like(d["x"], 777.0)
+    B.lasnet_sparse_bottleneck(d["x"], None, None, cfg.S, *U.weights(d), out=out_null)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.bits(out_list), U.bits(out_null))
+    # and a ratio at which runs of ~23 patches mix 5- and 6-block batches with cut ones
+    il = synth.make_index_list(cfg.N, cfg.G, cfg.GW, 0.75, seed=77)
+    _run_case(cfg, idx_np=il, use_masker=False)
+
+
 DENSE_CASES = [
     _cfg("tiny_f32"),
     _cfg("stage3_b128", N=2, name="dense_s3"),
