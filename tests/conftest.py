@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The tests load the library that is built in-tree; only where there is none (a fresh checkout) do
+    # they build it first (hipcc cross-compiles for gfx950 without a GPU).
+    from paper_2210_06223_amd import build
+    if not (os.path.exists(build.LIB) and os.path.exists(build.LIB_CHECK)):
+        build.build_all(verbose=False)
 
 
 def pytest_collection_modifyitems(config, items):
