@@ -105,7 +105,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
-    B.lib()  # fail loudly if the library is not built
+    from paper_2210_06223_amd import build as _build
+    if not os.path.exists(_build.LIB):            # a tree that was never built: build it, then load it
+        _build.build_all(verbose=False)
+    B.lib()  # fail loudly if the library cannot be loaded
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
